@@ -1,0 +1,138 @@
+/*
+ * tokenring.h - C ABI of the MI355X (gfx950) implementation of TokenRing's per-device
+ * compute path: blockwise attention, the log-sum-exp Update (merge), and the ring
+ * schedule of (Query chunk, K/V chunk) steps replayed on one GPU.
+ *
+ * Source of the operations: TokenRing (arXiv 2412.20501).
+ *   - Attention(Q, K, V) -> block_out, block_lse : Algorithm 1 and Sec. 3.2
+ *   - Update(block_out, block_lse) -> Out, Lse    : the two equations of Sec. 3.1
+ *   - iteration order of the steps                : Algorithm 1, walk-through of Sec. 3.3.1
+ *   - causal chunks                               : Sec. 3.3.2
+ *
+ * Conventions common to every call
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library never
+ *     allocates, frees or keeps device memory between calls.
+ *   - Layout is [B, H, S, D] with D contiguous; strides are in elements.  lse tensors
+ *     are [B, H, S] and use D = 1, stride_s = 1 normally.  (The paper's (N,H,D)/(H,N)
+ *     layout can be passed through the strides.)
+ *   - `hip_stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work on
+ *     it and return without synchronising.
+ *   - Every call validates its arguments first; on an error nothing is launched, the
+ *     status is returned and tr_last_error() describes it.  No exception crosses the ABI.
+ *   - Grouped-query attention: q.H must be a multiple of k.H; query head h reads K/V
+ *     head h / (q.H / k.H).
+ *   - lse is the natural-log log-sum-exp of the scaled scores.  A row with no allowed key
+ *     has out = 0 and lse = -inf, which is also the identity element of tr_merge.
+ */
+#ifndef TOKENRING_H
+#define TOKENRING_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TR_OK = 0,
+  TR_ERR_NULL = 1,        /* a required pointer is NULL                               */
+  TR_ERR_DTYPE = 2,       /* dtype not supported for that argument                    */
+  TR_ERR_SHAPE = 3,       /* shapes inconsistent or head dim unsupported              */
+  TR_ERR_STRIDE = 4,      /* stride too small for the shape, or misaligned            */
+  TR_ERR_ALIAS = 5,       /* accumulator and block tensors overlap                    */
+  TR_ERR_UNSUPPORTED = 6, /* valid request this build cannot run                      */
+  TR_ERR_WORKSPACE = 7,   /* workspace NULL, misaligned or too small                  */
+  TR_ERR_HIP = 8          /* a HIP runtime call failed (launch error)                 */
+} tr_status;
+
+typedef enum { TR_BF16 = 0, TR_F32 = 1 } tr_dtype;
+
+typedef enum {
+  TR_MASK_NONE = 0,        /* every key is visible                                    */
+  TR_MASK_CAUSAL_DIAG = 1  /* diagonal chunk: key index <= query index (needs Sq==Sk) */
+} tr_mask_kind;
+
+/* A strided view of device memory.  Element (b,h,s,d) is at
+ * ptr + (b*stride_b + h*stride_h + s*stride_s + d) elements of `dtype`. */
+typedef struct {
+  void* ptr;      /* device pointer; 16-byte aligned for bf16 Q/K/V and all out tensors */
+  int32_t dtype;  /* tr_dtype */
+  int64_t B, H, S, D;
+  int64_t stride_b, stride_h, stride_s;
+} tr_tensor;
+
+/*
+ * One block step of Algorithm 1 (Sec. 3.2): block_out, block_lse <- Attention(Q, K, V).
+ *   out[b,h,r,:] = sum_c softmax_c(scale * <q[b,h,r,:], k[b,g,c,:]>) v[b,g,c,:]
+ *   lse[b,h,r]   = ln sum_c exp(scale * <q[b,h,r,:], k[b,g,c,:]>)
+ * over the keys c the mask allows.
+ *   q   [B,Hq,Sq,D] bf16      k, v [B,Hkv,Sk,D] bf16      D in {64, 128}
+ *   out [B,Hq,Sq,D] bf16 or fp32 (written)                lse [B,Hq,Sq] fp32 (written)
+ * Sq and Sk are arbitrary (0 allowed; Sk == 0 gives out = 0, lse = -inf).
+ * Strides of q/k/v/out must be multiples of 8 elements (16-byte rows).
+ * Arithmetic: bf16 MFMA with fp32 accumulation, fp32 softmax, probabilities rounded to
+ * bf16 before the PV product.
+ */
+tr_status tr_block_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v,
+                        int mask_kind, float scale,
+                        const tr_tensor* out, const tr_tensor* lse, void* hip_stream);
+
+/*
+ * Block step with the causal rule at arbitrary chunk positions (Sec. 3.3.2; needed for
+ * the zigzag partition where a chunk is not aligned with the diagonal): query row r sits
+ * at sequence position q_pos0 + r, key c at k_pos0 + c, and key c is visible iff
+ * k_pos0 + c <= q_pos0 + r.  Rows that see no key get out = 0, lse = -inf.
+ * Same tensors as tr_block_attn; Sq and Sk need not be equal.
+ */
+tr_status tr_block_attn_causal_at(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v,
+                                  int64_t q_pos0, int64_t k_pos0, float scale,
+                                  const tr_tensor* out, const tr_tensor* lse, void* hip_stream);
+
+/*
+ * Out, Lse <- Update(block_out, block_lse), the two equations of Sec. 3.1, in place:
+ *   out_acc <- out_acc - sigmoid(block_lse - lse_acc) * (out_acc - block_out)
+ *   lse_acc <- lse_acc - ln(sigmoid(lse_acc - block_lse))
+ * evaluated as lse' = max + ln(1 + exp(-|diff|)) and w = exp(block_lse - lse') so that the
+ * identity element (out = 0, lse = -inf) on either side is exact and never yields NaN.
+ *   out_acc   [B,H,S,D] fp32 (read + written)    lse_acc   [B,H,S] fp32 (read + written)
+ *   block_out [B,H,S,D] fp32 or bf16 (read)      block_lse [B,H,S] fp32 (read)
+ * D must be a multiple of 4 (fp32 block) or 8 (bf16 block); any S (0 allowed).
+ * The accumulator tensors must not overlap the block tensors (TR_ERR_ALIAS).
+ */
+tr_status tr_merge(const tr_tensor* out_acc, const tr_tensor* lse_acc,
+                   const tr_tensor* block_out, const tr_tensor* block_lse, void* hip_stream);
+
+/*
+ * The whole schedule of Algorithm 1 on one GPU, without communication: Q, K, V are split
+ * into n_chunks chunks along S; for i in 0..n-1, for j in 0..n-1 the "device" j attends
+ * Query chunk c = (j - i) mod n to its K_j, V_j and the block result is merged into
+ * out[c], lse[c] with the Update above.  With causal != 0 (contiguous chunks, Sec. 3.3.2)
+ * steps with j > c are skipped and j == c uses the diagonal mask.
+ *   q [B,Hq,S,D] bf16   k, v [B,Hkv,S,D] bf16   out [B,Hq,S,D] fp32   lse [B,Hq,S] fp32
+ *   S must be a multiple of n_chunks; n_chunks >= 1; scale <= 0 selects 1/sqrt(D).
+ *   workspace: device memory of at least tr_ring_attn_workspace_bytes(q, n_chunks) bytes,
+ *   256-byte aligned, holding one fp32 block result (block_out, block_lse) between the
+ *   attention step and its merge.  Its contents on return are unspecified.
+ * The first block of every Query chunk is written straight into out/lse, so the caller
+ * need not initialise them.  All launches go to `hip_stream` in a fixed order, hence the
+ * result is bitwise reproducible.
+ */
+tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v,
+                       int n_chunks, int causal,
+                       const tr_tensor* out, const tr_tensor* lse, float scale,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of workspace tr_ring_attn needs for these shapes (0 on invalid arguments). */
+size_t tr_ring_attn_workspace_bytes(const tr_tensor* q, int n_chunks);
+
+/* Description of the last error on the calling thread ("" if none). Static storage. */
+const char* tr_last_error(void);
+
+/* Library version string, e.g. "tokenring-gfx950 0.1". Static storage. */
+const char* tr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOKENRING_H */

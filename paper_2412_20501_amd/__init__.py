@@ -1,0 +1,19 @@
+"""MI355X-native (gfx950) TokenRing per-device compute path: block attention, lse merge, ring schedule.
+
+Thin Python names over the C ABI in include/tokenring.h.  The first use of any name
+loads libtokenring.so and raises ImportError if it has not been built (there is no
+fallback path); `python -m paper_2412_20501_amd.build` compiles it.
+"""
+_EXPORTS = (
+    "LIB_PATH", "TR_BF16", "TR_F32", "TR_MASK_CAUSAL_DIAG", "TR_MASK_NONE", "TokenRingError", "TrTensor",
+    "desc", "raw_lib", "tr_block_attn", "tr_block_attn_causal_at", "tr_merge", "tr_ring_attn",
+    "tr_ring_attn_workspace_bytes", "tr_version",
+)
+__all__ = list(_EXPORTS)
+
+
+def __getattr__(name):
+    if name in _EXPORTS:
+        from . import _binding
+        return getattr(_binding, name)
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")

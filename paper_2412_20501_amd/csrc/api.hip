@@ -1,0 +1,251 @@
+// C ABI of libtokenring: argument validation, descriptor -> kernel-parameter marshalling,
+// and the host loop that replays TokenRing's Algorithm 1 on one GPU.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "tr_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+tr_status fail(tr_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+int64_t elem_bytes(int32_t dtype) { return dtype == TR_BF16 ? 2 : 4; }
+
+// Number of elements from ptr to one past the last addressed element of the view.
+int64_t extent_elems(const tr_tensor* t) {
+  if (t->B == 0 || t->H == 0 || t->S == 0 || t->D == 0) return 0;
+  return (t->B - 1) * t->stride_b + (t->H - 1) * t->stride_h + (t->S - 1) * t->stride_s + t->D;
+}
+
+bool overlaps(const tr_tensor* a, const tr_tensor* b) {
+  const int64_t ea = extent_elems(a) * elem_bytes(a->dtype), eb = extent_elems(b) * elem_bytes(b->dtype);
+  if (ea == 0 || eb == 0) return false;
+  const uintptr_t a0 = (uintptr_t)a->ptr, b0 = (uintptr_t)b->ptr;
+  return a0 < b0 + (uintptr_t)eb && b0 < a0 + (uintptr_t)ea;
+}
+
+// Common checks of one descriptor. `row_align` = required multiple (in elements) of the strides
+// and byte alignment of the pointer for vector access.
+tr_status check_tensor(const char* name, const tr_tensor* t, bool allow_bf16, bool allow_f32, int row_align_bytes) {
+  if (!t) return fail(TR_ERR_NULL, "%s: descriptor is NULL", name);
+  if (t->dtype != TR_BF16 && t->dtype != TR_F32) return fail(TR_ERR_DTYPE, "%s: unknown dtype %d", name, (int)t->dtype);
+  if ((t->dtype == TR_BF16 && !allow_bf16) || (t->dtype == TR_F32 && !allow_f32))
+    return fail(TR_ERR_DTYPE, "%s: dtype %s not supported for this argument", name, t->dtype == TR_BF16 ? "bf16" : "fp32");
+  if (t->B < 0 || t->H < 0 || t->S < 0 || t->D < 0) return fail(TR_ERR_SHAPE, "%s: negative dimension", name);
+  if (t->B > INT32_MAX || t->H > INT32_MAX || t->S > (1 << 30) || t->D > INT32_MAX)
+    return fail(TR_ERR_SHAPE, "%s: dimension too large", name);
+  const bool empty = extent_elems(t) == 0;
+  if (!empty && !t->ptr) return fail(TR_ERR_NULL, "%s: data pointer is NULL", name);
+  if (t->stride_b < 0 || t->stride_h < 0 || t->stride_s < 0) return fail(TR_ERR_STRIDE, "%s: negative stride", name);
+  if (!empty) {
+    if (t->S > 1 && t->stride_s < t->D) return fail(TR_ERR_STRIDE, "%s: stride_s %lld smaller than D %lld", name, (long long)t->stride_s, (long long)t->D);
+    const int64_t eb = elem_bytes(t->dtype);
+    if (row_align_bytes > 1) {
+      if (((uintptr_t)t->ptr) % row_align_bytes) return fail(TR_ERR_STRIDE, "%s: pointer not %d-byte aligned", name, row_align_bytes);
+      if ((t->stride_b * eb) % row_align_bytes || (t->stride_h * eb) % row_align_bytes || (t->stride_s * eb) % row_align_bytes)
+        return fail(TR_ERR_STRIDE, "%s: strides must be multiples of %d bytes", name, row_align_bytes);
+    }
+  }
+  return TR_OK;
+}
+
+tr_status attn_common(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int causal, int64_t off64, float scale,
+                      const tr_tensor* out, const tr_tensor* lse, void* stream) {
+  tr_status st;
+  if ((st = check_tensor("q", q, true, false, 16)) != TR_OK) return st;
+  if ((st = check_tensor("k", k, true, false, 16)) != TR_OK) return st;
+  if ((st = check_tensor("v", v, true, false, 16)) != TR_OK) return st;
+  if ((st = check_tensor("out", out, true, true, 16)) != TR_OK) return st;
+  if ((st = check_tensor("lse", lse, false, true, 4)) != TR_OK) return st;
+  if (q->D != 64 && q->D != 128) return fail(TR_ERR_SHAPE, "head dim %lld not supported (64 or 128)", (long long)q->D);
+  if (k->D != q->D || v->D != q->D || out->D != q->D) return fail(TR_ERR_SHAPE, "head dims of q, k, v, out differ");
+  if (lse->D != 1) return fail(TR_ERR_SHAPE, "lse must have D = 1");
+  if (k->B != q->B || v->B != q->B || out->B != q->B || lse->B != q->B) return fail(TR_ERR_SHAPE, "batch sizes differ");
+  if (k->H != v->H || k->S != v->S) return fail(TR_ERR_SHAPE, "k and v shapes differ");
+  if (out->H != q->H || lse->H != q->H || out->S != q->S || lse->S != q->S) return fail(TR_ERR_SHAPE, "out/lse shape does not match q");
+  if (q->H > 0 && (k->H <= 0 || q->H % k->H)) return fail(TR_ERR_SHAPE, "query heads %lld not a multiple of K/V heads %lld", (long long)q->H, (long long)k->H);
+  if (!(scale > 0.f) || !isfinite(scale)) return fail(TR_ERR_UNSUPPORTED, "scale must be finite and > 0");
+  if (overlaps(out, q) || overlaps(out, k) || overlaps(out, v) || overlaps(lse, q) || overlaps(lse, k) || overlaps(lse, v) || overlaps(out, lse))
+    return fail(TR_ERR_ALIAS, "outputs overlap inputs or each other");
+  if ((int64_t)q->B * q->H > (1 << 24)) return fail(TR_ERR_SHAPE, "too many (batch, head) pairs");
+
+  tr::AttnParams p;
+  memset(&p, 0, sizeof(p));
+  p.q = (const __bf16*)q->ptr; p.k = (const __bf16*)k->ptr; p.v = (const __bf16*)v->ptr;
+  p.out = out->ptr; p.lse = (float*)lse->ptr;
+  p.q_sb = q->stride_b; p.q_sh = q->stride_h; p.q_ss = q->stride_s;
+  p.k_sb = k->stride_b; p.k_sh = k->stride_h; p.k_ss = k->stride_s;
+  p.v_sb = v->stride_b; p.v_sh = v->stride_h; p.v_ss = v->stride_s;
+  p.o_sb = out->stride_b; p.o_sh = out->stride_h; p.o_ss = out->stride_s;
+  p.l_sb = lse->stride_b; p.l_sh = lse->stride_h; p.l_ss = lse->stride_s;
+  p.B = (int)q->B; p.Hq = (int)q->H; p.Hkv = (int)k->H; p.Sq = (int)q->S; p.Sk = (int)k->S;
+  p.causal = causal ? 1 : 0;
+  const int64_t lim = (int64_t)1 << 30;
+  p.causal_off = (int)(off64 > lim ? lim : (off64 < -lim ? -lim : off64));
+  p.scale = scale;
+  const int bm = tr::attn_rows_per_block();
+  p.n_qtiles = (p.Sq + bm - 1) / bm;
+  p.xcd_map = (p.B * p.Hkv) % 8 == 0 && (int64_t)p.n_qtiles * p.B * p.Hq >= 8;
+  if (p.B == 0 || p.Hq == 0 || p.Sq == 0) return TR_OK;
+  const hipError_t e = tr::launch_block_attn(p, (int)q->D, out->dtype == TR_F32, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(TR_ERR_HIP, "block attention launch failed: %s", hipGetErrorString(e));
+  return TR_OK;
+}
+
+// View of chunk `c` (of length C along S) of a tensor.
+tr_tensor chunk_view(const tr_tensor* t, int64_t c, int64_t C) {
+  tr_tensor r = *t;
+  r.ptr = (char*)t->ptr + c * C * t->stride_s * elem_bytes(t->dtype);
+  r.S = C;
+  return r;
+}
+
+constexpr size_t kWsAlign = 256;
+size_t align_up(size_t x) { return (x + kWsAlign - 1) / kWsAlign * kWsAlign; }
+
+}  // namespace
+
+extern "C" {
+
+const char* tr_last_error(void) { return g_err; }
+const char* tr_version(void) { return "tokenring-gfx950 0.1"; }
+
+tr_status tr_block_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int mask_kind, float scale,
+                        const tr_tensor* out, const tr_tensor* lse, void* hip_stream) {
+  g_err[0] = 0;
+  if (mask_kind != TR_MASK_NONE && mask_kind != TR_MASK_CAUSAL_DIAG) return fail(TR_ERR_UNSUPPORTED, "unknown mask kind %d", mask_kind);
+  if (mask_kind == TR_MASK_CAUSAL_DIAG && q && k && q->S != k->S)
+    return fail(TR_ERR_SHAPE, "the diagonal causal mask needs Sq == Sk (got %lld, %lld)", (long long)q->S, (long long)k->S);
+  return attn_common(q, k, v, mask_kind == TR_MASK_CAUSAL_DIAG, 0, scale, out, lse, hip_stream);
+}
+
+tr_status tr_block_attn_causal_at(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int64_t q_pos0, int64_t k_pos0,
+                                  float scale, const tr_tensor* out, const tr_tensor* lse, void* hip_stream) {
+  g_err[0] = 0;
+  if (q_pos0 < 0 || k_pos0 < 0) return fail(TR_ERR_SHAPE, "chunk positions must be >= 0");
+  return attn_common(q, k, v, 1, q_pos0 - k_pos0, scale, out, lse, hip_stream);
+}
+
+tr_status tr_merge(const tr_tensor* out_acc, const tr_tensor* lse_acc, const tr_tensor* block_out, const tr_tensor* block_lse,
+                   void* hip_stream) {
+  g_err[0] = 0;
+  tr_status st;
+  if ((st = check_tensor("out_acc", out_acc, false, true, 16)) != TR_OK) return st;
+  if ((st = check_tensor("lse_acc", lse_acc, false, true, 4)) != TR_OK) return st;
+  if ((st = check_tensor("block_out", block_out, true, true, 8)) != TR_OK) return st;
+  if ((st = check_tensor("block_lse", block_lse, false, true, 4)) != TR_OK) return st;
+  if (block_out->dtype == TR_F32 && (st = check_tensor("block_out", block_out, true, true, 16)) != TR_OK) return st;
+  if (lse_acc->D != 1 || block_lse->D != 1) return fail(TR_ERR_SHAPE, "lse tensors must have D = 1");
+  if (out_acc->D % 4) return fail(TR_ERR_SHAPE, "D = %lld must be a multiple of 4", (long long)out_acc->D);
+  if (block_out->B != out_acc->B || block_out->H != out_acc->H || block_out->S != out_acc->S || block_out->D != out_acc->D)
+    return fail(TR_ERR_SHAPE, "block_out shape does not match out_acc");
+  if (lse_acc->B != out_acc->B || lse_acc->H != out_acc->H || lse_acc->S != out_acc->S) return fail(TR_ERR_SHAPE, "lse_acc shape does not match out_acc");
+  if (block_lse->B != out_acc->B || block_lse->H != out_acc->H || block_lse->S != out_acc->S) return fail(TR_ERR_SHAPE, "block_lse shape does not match out_acc");
+  if (overlaps(out_acc, block_out) || overlaps(out_acc, block_lse) || overlaps(lse_acc, block_out) || overlaps(lse_acc, block_lse) || overlaps(out_acc, lse_acc))
+    return fail(TR_ERR_ALIAS, "accumulator and block tensors overlap");
+  if ((int64_t)out_acc->B * out_acc->H * out_acc->S >= ((int64_t)1 << 32))
+    return fail(TR_ERR_SHAPE, "too many elements for one launch");
+
+  tr::MergeParams p;
+  memset(&p, 0, sizeof(p));
+  p.acc_out = (float*)out_acc->ptr; p.acc_lse = (float*)lse_acc->ptr;
+  p.blk_out = block_out->ptr; p.blk_lse = (const float*)block_lse->ptr;
+  p.ao_sb = out_acc->stride_b; p.ao_sh = out_acc->stride_h; p.ao_ss = out_acc->stride_s;
+  p.al_sb = lse_acc->stride_b; p.al_sh = lse_acc->stride_h; p.al_ss = lse_acc->stride_s;
+  p.bo_sb = block_out->stride_b; p.bo_sh = block_out->stride_h; p.bo_ss = block_out->stride_s;
+  p.bl_sb = block_lse->stride_b; p.bl_sh = block_lse->stride_h; p.bl_ss = block_lse->stride_s;
+  p.B = (int)out_acc->B; p.H = (int)out_acc->H; p.S = (int)out_acc->S; p.D = (int)out_acc->D;
+  auto dense = [](const tr_tensor* t) {
+    return t->stride_s == t->D && t->stride_h == t->S * t->D && t->stride_b == t->H * t->S * t->D;
+  };
+  p.contiguous = dense(out_acc) && dense(block_out) && dense(lse_acc) && dense(block_lse);
+  if (p.B == 0 || p.H == 0 || p.S == 0 || p.D == 0) return TR_OK;
+  const hipError_t e = tr::launch_merge(p, block_out->dtype == TR_BF16, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail(TR_ERR_HIP, "merge launch failed: %s", hipGetErrorString(e));
+  return TR_OK;
+}
+
+size_t tr_ring_attn_workspace_bytes(const tr_tensor* q, int n_chunks) {
+  if (!q || n_chunks < 1 || q->B < 0 || q->H < 0 || q->S < 0 || q->D < 0 || q->S % n_chunks) return 0;
+  const size_t C = (size_t)(q->S / n_chunks);
+  const size_t rows = (size_t)q->B * (size_t)q->H * C;
+  return align_up(rows * (size_t)q->D * 4) + align_up(rows * 4);
+}
+
+tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int n_chunks, int causal,
+                       const tr_tensor* out, const tr_tensor* lse, float scale, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+  g_err[0] = 0;
+  if (!q || !k || !v || !out || !lse) return fail(TR_ERR_NULL, "a tensor descriptor is NULL");
+  if (n_chunks < 1) return fail(TR_ERR_SHAPE, "n_chunks must be >= 1");
+  if (q->S < 0 || q->S % n_chunks) return fail(TR_ERR_SHAPE, "sequence length %lld is not a multiple of n_chunks %d", (long long)q->S, n_chunks);
+  if (k->S != q->S || v->S != q->S) return fail(TR_ERR_SHAPE, "q, k, v must have the same sequence length");
+  if (out->dtype != TR_F32) return fail(TR_ERR_DTYPE, "out must be fp32 (it is the merge accumulator)");
+  if (q->D > 0 && !(scale > 0.f)) scale = 1.0f / sqrtf((float)q->D);
+  const int64_t C = q->S / n_chunks;
+
+  // Validate every argument once through the single-step checks (chunk 0 views have the
+  // same strides, dtypes and alignment class as all others).
+  tr_status st;
+  if ((st = check_tensor("q", q, true, false, 16)) != TR_OK) return st;
+  if ((st = check_tensor("k", k, true, false, 16)) != TR_OK) return st;
+  if ((st = check_tensor("v", v, true, false, 16)) != TR_OK) return st;
+  if ((st = check_tensor("out", out, false, true, 16)) != TR_OK) return st;
+  if ((st = check_tensor("lse", lse, false, true, 4)) != TR_OK) return st;
+  if (out->B != q->B || out->H != q->H || out->S != q->S || out->D != q->D || lse->B != q->B || lse->H != q->H || lse->S != q->S || lse->D != 1)
+    return fail(TR_ERR_SHAPE, "out/lse shape does not match q");
+
+  const size_t need = tr_ring_attn_workspace_bytes(q, n_chunks);
+  const size_t rows = (size_t)q->B * (size_t)q->H * (size_t)C;
+  tr_tensor ws_out, ws_lse;
+  memset(&ws_out, 0, sizeof(ws_out));
+  if (n_chunks > 1 && rows > 0) {
+    if (!workspace) return fail(TR_ERR_WORKSPACE, "workspace is NULL (need %zu bytes)", need);
+    if (((uintptr_t)workspace) % kWsAlign) return fail(TR_ERR_WORKSPACE, "workspace must be %zu-byte aligned", kWsAlign);
+    if (workspace_bytes < need) return fail(TR_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, need);
+    ws_out.ptr = workspace; ws_out.dtype = TR_F32;
+    ws_out.B = q->B; ws_out.H = q->H; ws_out.S = C; ws_out.D = q->D;
+    ws_out.stride_s = q->D; ws_out.stride_h = C * q->D; ws_out.stride_b = q->H * C * q->D;
+    ws_lse = ws_out;
+    ws_lse.ptr = (char*)workspace + align_up(rows * (size_t)q->D * 4);
+    ws_lse.D = 1; ws_lse.stride_s = 1; ws_lse.stride_h = C; ws_lse.stride_b = q->H * C;
+    tr_tensor ws_all = ws_out;  // alias check of the whole workspace against the user tensors
+    ws_all.B = 1; ws_all.H = 1; ws_all.S = 1; ws_all.D = (int64_t)(need / 4);
+    if (overlaps(&ws_all, q) || overlaps(&ws_all, k) || overlaps(&ws_all, v) || overlaps(&ws_all, out) || overlaps(&ws_all, lse))
+      return fail(TR_ERR_ALIAS, "workspace overlaps a tensor argument");
+  }
+
+  // Algorithm 1 replayed on one device: iteration i, "device" j, Query chunk c = (j - i) mod n.
+  for (int i = 0; i < n_chunks; i++) {
+    for (int j = 0; j < n_chunks; j++) {
+      const int c = ((j - i) % n_chunks + n_chunks) % n_chunks;
+      if (causal && j > c) continue;
+      const tr_tensor qc = chunk_view(q, c, C), kj = chunk_view(k, j, C), vj = chunk_view(v, j, C);
+      const tr_tensor oc = chunk_view(out, c, C), lc = chunk_view(lse, c, C);
+      const int diag = causal && j == c;
+      if (i == 0) {
+        // first block of Query chunk c: it *is* the accumulator's initial value
+        st = attn_common(&qc, &kj, &vj, diag, 0, scale, &oc, &lc, hip_stream);
+        if (st != TR_OK) return st;
+      } else {
+        st = attn_common(&qc, &kj, &vj, diag, 0, scale, &ws_out, &ws_lse, hip_stream);
+        if (st != TR_OK) return st;
+        st = tr_merge(&oc, &lc, &ws_out, &ws_lse, hip_stream);
+        if (st != TR_OK) return st;
+      }
+    }
+  }
+  return TR_OK;
+}
+
+}  // extern "C"

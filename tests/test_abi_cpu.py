@@ -1,0 +1,115 @@
+"""The C-ABI library on a machine without a GPU: it loads, exports every declared symbol,
+and rejects bad arguments before any launch (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "tokenring.h")
+
+
+@pytest.fixture(scope="module")
+def tr():
+    import paper_2412_20501_amd as m
+    m.raw_lib()
+    return m
+
+
+def _t(tr, dtype, B, H, S, D, ptr=0x7F0000000000, strides=None):
+    sb, sh, ss = strides if strides else (H * S * D, S * D, D)
+    return tr.TrTensor(ptr, dtype, B, H, S, D, sb, sh, ss)
+
+
+def test_every_declared_symbol_is_exported(tr):
+    text = open(HEADER).read()
+    names = set(re.findall(r"\b(tr_[a-z_]+)\s*\(", text))
+    assert {"tr_block_attn", "tr_block_attn_causal_at", "tr_merge", "tr_ring_attn",
+            "tr_ring_attn_workspace_bytes", "tr_last_error", "tr_version"} <= names
+    lib = ctypes.CDLL(tr.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in tokenring.h but not exported"
+    assert tr.tr_version().startswith("tokenring-gfx950")
+
+
+def test_struct_layout_matches_header(tr):
+    assert ctypes.sizeof(tr.TrTensor) == 8 + 8 + 7 * 8      # ptr, dtype (+pad), 7 x int64
+    assert tr.TrTensor.B.offset == 16 and tr.TrTensor.stride_s.offset == 64
+
+
+def _status(tr, fn, *args):
+    st = fn(*args)
+    return st, tr.raw_lib().tr_last_error().decode()
+
+
+def test_block_attn_rejects_bad_arguments(tr):
+    lib = tr.raw_lib()
+    q = _t(tr, tr.TR_BF16, 1, 4, 128, 128); k = _t(tr, tr.TR_BF16, 1, 2, 128, 128, ptr=0x7F1000000000)
+    v = _t(tr, tr.TR_BF16, 1, 2, 128, 128, ptr=0x7F2000000000)
+    o = _t(tr, tr.TR_F32, 1, 4, 128, 128, ptr=0x7F3000000000); l = _t(tr, tr.TR_F32, 1, 4, 128, 1, ptr=0x7F4000000000)
+    B = ctypes.byref
+    call = lambda q=q, k=k, v=v, m=0, s=0.1, o=o, l=l: _status(tr, lib.tr_block_attn, B(q), B(k), B(v), m, s, B(o), B(l), None)
+    assert call(q=_t(tr, tr.TR_BF16, 1, 4, 128, 128, ptr=None))[0] == 1                     # NULL data
+    assert lib.tr_block_attn(None, B(k), B(v), 0, 0.1, B(o), B(l), None) == 1              # NULL descriptor
+    assert call(q=_t(tr, tr.TR_F32, 1, 4, 128, 128))[0] == 2                                # q must be bf16
+    assert call(l=_t(tr, tr.TR_BF16, 1, 4, 128, 1, ptr=0x7F4000000000))[0] == 2             # lse must be fp32
+    st, msg = call(q=_t(tr, tr.TR_BF16, 1, 4, 128, 96), o=_t(tr, tr.TR_F32, 1, 4, 128, 96, ptr=0x7F3000000000))
+    assert st == 3 and "head dim" in msg
+    assert call(k=_t(tr, tr.TR_BF16, 1, 3, 128, 128, ptr=0x7F1000000000), v=_t(tr, tr.TR_BF16, 1, 3, 128, 128, ptr=0x7F2000000000))[0] == 3   # 4 % 3
+    assert call(v=_t(tr, tr.TR_BF16, 1, 2, 64, 128, ptr=0x7F2000000000))[0] == 3            # k/v length differ
+    assert call(o=_t(tr, tr.TR_F32, 1, 4, 127, 128, ptr=0x7F3000000000))[0] == 3            # out shape
+    assert call(m=1, k=_t(tr, tr.TR_BF16, 1, 2, 64, 128, ptr=0x7F1000000000), v=_t(tr, tr.TR_BF16, 1, 2, 64, 128, ptr=0x7F2000000000))[0] == 3  # diag needs Sq == Sk
+    assert call(m=7)[0] == 6                                                                # unknown mask
+    assert call(s=0.0)[0] == 6 and call(s=float("nan"))[0] == 6                             # scale
+    assert call(q=_t(tr, tr.TR_BF16, 1, 4, 128, 128, strides=(4 * 128 * 128, 128 * 128, 100)))[0] == 4   # stride_s < D
+    assert call(q=_t(tr, tr.TR_BF16, 1, 4, 128, 128, strides=(4 * 128 * 132, 128 * 132, 132)))[0] == 4   # rows not 16-byte multiples
+    assert call(q=_t(tr, tr.TR_BF16, 1, 4, 128, 128, ptr=0x7F0000000002))[0] == 4           # misaligned pointer
+    assert call(o=_t(tr, tr.TR_F32, 1, 4, 128, 128, ptr=0x7F0000000000))[0] == 5            # out aliases q
+    assert lib.tr_block_attn_causal_at(B(q), B(k), B(v), -1, 0, 0.1, B(o), B(l), None) == 3
+
+
+def test_merge_rejects_bad_arguments(tr):
+    lib = tr.raw_lib()
+    B = ctypes.byref
+    ao = _t(tr, tr.TR_F32, 1, 2, 64, 128); al = _t(tr, tr.TR_F32, 1, 2, 64, 1, ptr=0x7F1000000000)
+    bo = _t(tr, tr.TR_F32, 1, 2, 64, 128, ptr=0x7F2000000000); bl = _t(tr, tr.TR_F32, 1, 2, 64, 1, ptr=0x7F3000000000)
+    call = lambda ao=ao, al=al, bo=bo, bl=bl: _status(tr, lib.tr_merge, B(ao), B(al), B(bo), B(bl), None)
+    assert call(ao=_t(tr, tr.TR_BF16, 1, 2, 64, 128))[0] == 2                               # accumulator must be fp32
+    assert call(bl=_t(tr, tr.TR_BF16, 1, 2, 64, 1, ptr=0x7F3000000000))[0] == 2
+    assert call(bo=_t(tr, tr.TR_F32, 1, 2, 63, 128, ptr=0x7F2000000000))[0] == 3
+    assert call(al=_t(tr, tr.TR_F32, 1, 2, 64, 2, ptr=0x7F1000000000))[0] == 3
+    assert call(ao=_t(tr, tr.TR_F32, 1, 2, 64, 6), bo=_t(tr, tr.TR_F32, 1, 2, 64, 6, ptr=0x7F2000000000))[0] in (3, 4)   # D % 4
+    st, msg = call(bo=_t(tr, tr.TR_F32, 1, 2, 64, 128, ptr=0x7F0000000100))
+    assert st == 5 and "overlap" in msg                                                     # block aliases accumulator
+    assert lib.tr_merge(None, B(al), B(bo), B(bl), None) == 1
+
+
+def test_ring_attn_rejects_bad_arguments_and_workspace_size(tr):
+    lib = tr.raw_lib()
+    B = ctypes.byref
+    q = _t(tr, tr.TR_BF16, 1, 32, 32768, 128); k = _t(tr, tr.TR_BF16, 1, 32, 32768, 128, ptr=0x7F1000000000)
+    v = _t(tr, tr.TR_BF16, 1, 32, 32768, 128, ptr=0x7F2000000000)
+    o = _t(tr, tr.TR_F32, 1, 32, 32768, 128, ptr=0x7F3000000000); l = _t(tr, tr.TR_F32, 1, 32, 32768, 1, ptr=0x7F5000000000)
+    need = lib.tr_ring_attn_workspace_bytes(B(q), 8)
+    assert need == 32 * 4096 * 128 * 4 + 32 * 4096 * 4            # one fp32 block_out + block_lse
+    assert lib.tr_ring_attn_workspace_bytes(B(q), 7) == 0 and lib.tr_ring_attn_workspace_bytes(None, 8) == 0
+    ws = 0x7F7000000000
+    call = lambda q=q, k=k, v=v, n=8, o=o, l=l, ws=ws, nb=need: _status(
+        tr, lib.tr_ring_attn, B(q), B(k), B(v), n, 1, B(o), B(l), 0.0, ws, nb, None)
+    assert call(n=0)[0] == 3 and call(n=7)[0] == 3                                          # S % n_chunks
+    assert call(o=_t(tr, tr.TR_BF16, 1, 32, 32768, 128, ptr=0x7F3000000000))[0] == 2         # out must be fp32
+    assert call(k=_t(tr, tr.TR_BF16, 1, 32, 4096, 128, ptr=0x7F1000000000))[0] == 3
+    assert call(ws=None)[0] == 7 and call(nb=need - 1)[0] == 7 and call(ws=ws + 16)[0] == 7
+    st, msg = call(ws=0x7F3000000000)
+    assert st == 5 and "workspace" in msg
+
+
+def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
+    """No fallback: a missing libtokenring.so is an ImportError, not a silent CPU path."""
+    import importlib
+    import paper_2412_20501_amd._binding as b
+    monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        b._load()
+    importlib.reload(b)

@@ -1,0 +1,72 @@
+"""Full-size single-step and merge-only workloads in the launch configuration bench.py times."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from gpu_util import bits_to_dev, f64, max_abs, to_np
+
+pytestmark = pytest.mark.gpu
+OUT_TOL, LSE_TOL, MERGE_TOL = 1e-2, 1e-3, 1e-5
+
+
+@pytest.mark.parametrize("name", ["cfg2_block", "cfg2_block_diag"])
+def test_config2_block_step_4096x4096(lib, name):
+    """bf16 block_out + fp32 block_lse.  Four heads are checked in full, the rest on sampled rows.
+
+    block_out is rounded to bf16 on output, so its error against the oracle includes half a
+    bf16 ulp of the value itself (up to 2^-9 relative); it is also reported against the
+    oracle rounded to bf16.
+    """
+    cfg = wl.CONFIGS[name]
+    qb, kb, vb = wl.make_qkv_bits(cfg)
+    q, k, v = bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb)
+    out = torch.empty((cfg.B, cfg.Hq, cfg.S, cfg.D), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((cfg.B, cfg.Hq, cfg.S), dtype=torch.float32, device="cuda")
+    mask = lib.TR_MASK_CAUSAL_DIAG if cfg.causal else lib.TR_MASK_NONE
+    lib.tr_block_attn(q, k, v, mask, cfg.scale, out, lse)
+    torch.cuda.synchronize()
+    full_heads = [0, 13, 22, 31]
+    worst_o = worst_l = worst_o_rounded = 0.0
+    for h in full_heads:
+        ref_o, ref_l = oracle.attention_block(f64(qb[:, h:h + 1]), f64(kb[:, h:h + 1]), f64(vb[:, h:h + 1]), cfg.scale,
+                                              causal_diag=cfg.causal)
+        o = to_np(out[:, h:h + 1])
+        worst_o = max(worst_o, max_abs(o, ref_o))
+        worst_l = max(worst_l, max_abs(to_np(lse[:, h:h + 1]), ref_l))
+        ref_bf16 = wl.bf16_bits_to_f64(wl.f32_to_bf16_bits(ref_o.astype(np.float32)))
+        worst_o_rounded = max(worst_o_rounded, max_abs(o, ref_bf16))
+    rows = wl.sample_rows(cfg.S, 256, 64, seed=cfg.seed + 1)
+    ridx = torch.from_numpy(rows).to("cuda")
+    for h in range(cfg.Hq):
+        if h in full_heads:
+            continue
+        ref_o, ref_l = oracle.attention_rows(f64(qb[0, h][rows]), rows, f64(kb[0, h]), f64(vb[0, h]), cfg.scale, cfg.causal)
+        worst_o = max(worst_o, max_abs(to_np(out[0, h][ridx]), ref_o))
+        worst_l = max(worst_l, max_abs(to_np(lse[0, h][ridx]), ref_l))
+    print(f"{name}: max|d out| {worst_o:.3e} (vs bf16-rounded oracle {worst_o_rounded:.3e}), max|d lse| {worst_l:.3e}")
+    assert worst_o <= OUT_TOL and worst_l <= LSE_TOL
+
+
+def test_config4_merge_full_size_sampled_rows(lib):
+    """Eight [1,32,32768,128] fp32 partials merged in ring order; oracle on sampled rows of every head."""
+    cfg = wl.CONFIGS["cfg4_merge"]
+    outs, lses = wl.make_merge_partials(cfg)
+    acc_o = torch.zeros((cfg.B, cfg.H, cfg.S, cfg.D), dtype=torch.float32, device="cuda")
+    acc_l = torch.full((cfg.B, cfg.H, cfg.S), float("-inf"), dtype=torch.float32, device="cuda")
+    for i in range(cfg.n_partials):
+        blk_o, blk_l = torch.from_numpy(outs[i]).to("cuda"), torch.from_numpy(lses[i]).to("cuda")
+        lib.tr_merge(acc_o, acc_l, blk_o, blk_l)
+        torch.cuda.synchronize()
+        del blk_o, blk_l
+    rows = wl.sample_rows(cfg.S, 4096, 512, seed=cfg.seed + 1)
+    ref_o, ref_l = oracle.merge_nary([o[:, :, rows] for o in outs], [l[:, :, rows] for l in lses])
+    ridx = torch.from_numpy(rows).to("cuda")
+    d_o, d_l = max_abs(to_np(acc_o[:, :, ridx]), ref_o), max_abs(to_np(acc_l[:, :, ridx]), ref_l)
+    print(f"cfg4: {len(rows)} rows x {cfg.H} heads, max|d out| {d_o:.3e}, max|d lse| {d_l:.3e}")
+    assert d_o <= MERGE_TOL and d_l <= MERGE_TOL
+    # properties that hold at any size: lse_acc >= every partial lse; no NaN anywhere
+    assert not torch.isnan(acc_o).any() and not torch.isnan(acc_l).any()
+    for l in lses:
+        assert torch.all(acc_l >= torch.from_numpy(l).to("cuda"))

@@ -1,0 +1,101 @@
+"""GPU parity of tr_ring_attn (Algorithm 1's schedule on one GPU) against the fp64 oracle.
+
+The reference is *unchunked* fp64 attention: the chunked schedule must reach it within
+max-abs 1e-2 on out and 1e-3 on lse.  The large workloads are checked on a row sample
+(all heads; first rows, every chunk boundary -1/0/+1, last rows, seeded random rows),
+each sampled row computed exactly by the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from gpu_util import bits_to_dev, f64, max_abs, rand_bits, to_np
+
+pytestmark = pytest.mark.gpu
+OUT_TOL, LSE_TOL = 1e-2, 1e-3
+
+
+def _ring(lib, q, k, v, n_chunks, causal, scale=0.0, poison=True):
+    B, Hq, S, D = q.shape
+    fill = float("nan") if poison else 0.0
+    out = torch.full((B, Hq, S, D), fill, dtype=torch.float32, device="cuda")
+    lse = torch.full((B, Hq, S), fill, dtype=torch.float32, device="cuda")
+    ws = torch.empty(lib.tr_ring_attn_workspace_bytes(q, n_chunks), dtype=torch.uint8, device="cuda")
+    lib.tr_ring_attn(q, k, v, n_chunks, causal, out, lse, scale, ws)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def test_ring_config1_small_noncausal_16_steps(lib):
+    cfg = wl.CONFIGS["cfg1_small"]
+    qb, kb, vb = wl.make_qkv_bits(cfg)
+    out, lse = _ring(lib, bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb), cfg.n_chunks, cfg.causal, cfg.scale)
+    ref_o, ref_l = oracle.attention_full(f64(qb), f64(kb), f64(vb), cfg.scale, causal=False)
+    assert max_abs(to_np(out), ref_o) <= OUT_TOL and max_abs(to_np(lse), ref_l) <= LSE_TOL
+    # the oracle's own replay of Algorithm 1 agrees with the same tolerance
+    alg_o, alg_l = oracle.ring_attention(f64(qb), f64(kb), f64(vb), cfg.n_chunks, False, cfg.scale)
+    assert max_abs(to_np(out), alg_o) <= OUT_TOL and max_abs(to_np(lse), alg_l) <= LSE_TOL
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("n_chunks", [1, 2, 3, 8])
+def test_ring_chunk_count_invariance(lib, n_chunks, causal):
+    B, Hq, Hkv, S, D = 2, 4, 2, 384, 128          # chunk of 128 / 48: several waves and a ragged tile tail
+    qb, kb, vb = rand_bits((B, Hq, S, D), 21), rand_bits((B, Hkv, S, D), 22), rand_bits((B, Hkv, S, D), 23)
+    out, lse = _ring(lib, bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb), n_chunks, causal)   # scale 0 -> 1/sqrt(D)
+    ref_o, ref_l = oracle.attention_full(f64(qb), f64(kb), f64(vb), 1.0 / np.sqrt(D), causal)
+    assert max_abs(to_np(out), ref_o) <= OUT_TOL and max_abs(to_np(lse), ref_l) <= LSE_TOL
+
+
+def test_ring_n1_equals_single_block_step_bitwise(lib):
+    qb, kb, vb = rand_bits((1, 2, 320, 128), 24), rand_bits((1, 2, 320, 128), 25), rand_bits((1, 2, 320, 128), 26)
+    q, k, v = bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb)
+    out, lse = _ring(lib, q, k, v, 1, True, 0.07)
+    o2 = torch.empty_like(out); l2 = torch.empty_like(lse)
+    lib.tr_block_attn(q, k, v, lib.TR_MASK_CAUSAL_DIAG, 0.07, o2, l2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, o2) and torch.equal(lse, l2)
+
+
+def test_ring_is_bitwise_reproducible(lib):
+    qb, kb, vb = rand_bits((1, 4, 512, 64), 27), rand_bits((1, 4, 512, 64), 28), rand_bits((1, 4, 512, 64), 29)
+    q, k, v = bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb)
+    a = _ring(lib, q, k, v, 4, True)
+    b = _ring(lib, q, k, v, 4, True, poison=False)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def _check_rows(cfg, out, lse, qb, kb, vb, n_random, heads=None):
+    """Compare sampled rows of every head against exact oracle rows."""
+    rows = wl.sample_rows(cfg.S, cfg.chunk, n_random, seed=cfg.seed + 1)
+    G = cfg.Hq // cfg.Hkv
+    worst_o = worst_l = 0.0
+    ridx = torch.from_numpy(rows).to("cuda")
+    for h in (range(cfg.Hq) if heads is None else heads):
+        g = h // G
+        ref_o, ref_l = oracle.attention_rows(f64(qb[0, h][rows]), rows, f64(kb[0, g]), f64(vb[0, g]), cfg.scale, cfg.causal)
+        worst_o = max(worst_o, max_abs(to_np(out[0, h][ridx]), ref_o))
+        worst_l = max(worst_l, max_abs(to_np(lse[0, h][ridx]), ref_l))
+    return worst_o, worst_l, len(rows)
+
+
+def test_ring_config3_causal_32k_8_chunks_sampled_rows(lib):
+    cfg = wl.CONFIGS["cfg3_ring"]
+    qb, kb, vb = wl.make_qkv_bits(cfg)
+    out, lse = _ring(lib, bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb), cfg.n_chunks, cfg.causal, cfg.scale)
+    assert not torch.isnan(out).any() and not torch.isnan(lse).any()
+    worst_o, worst_l, n = _check_rows(cfg, out, lse, qb, kb, vb, n_random=256)
+    print(f"cfg3: {n} rows x {cfg.Hq} heads, max|d out| {worst_o:.3e}, max|d lse| {worst_l:.3e}")
+    assert worst_o <= OUT_TOL and worst_l <= LSE_TOL
+
+
+def test_ring_config5_gqa_128k_16_chunks_sampled_rows(lib):
+    cfg = wl.CONFIGS["cfg5_gqa"]
+    qb, kb, vb = wl.make_qkv_bits(cfg)
+    out, lse = _ring(lib, bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb), cfg.n_chunks, cfg.causal, cfg.scale)
+    assert not torch.isnan(lse).any()
+    worst_o, worst_l, n = _check_rows(cfg, out, lse, qb, kb, vb, n_random=96)
+    print(f"cfg5: {n} rows x {cfg.Hq} heads, max|d out| {worst_o:.3e}, max|d lse| {worst_l:.3e}")
+    assert worst_o <= OUT_TOL and worst_l <= LSE_TOL
