@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the TokenRing per-device compute path on one MI355X.
+
+One JSON line on stdout.  A *step* is one iteration of Algorithm 1 on one device at the
+4096 x 4096, 32-head, D=128 block shape: tr_block_attn (bf16 block_out + fp32 block_lse)
+followed by tr_merge of that block into the fp32 accumulators.  `value` is the step's
+attention TFLOP (4*Sq*Sk*D per head) divided by the whole step time, inputs resident in
+HBM.  `roofline` is the block-attention kernel against the bf16 MFMA peak, from HIP-event
+durations recorded around every launch of the timed region; `merge_roofline` is the same
+for the merge kernel against HBM.  `extras` adds the merge-only bandwidth workload and the
+two ring-schedule workloads.  `cpu_baseline` times the fp64 oracle on a few heads of the
+same block step on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def _dev(bits):
+    import numpy as np
+    import torch
+    return torch.from_numpy(bits.view(np.int16)).to("cuda").view(torch.bfloat16)
+
+
+def _event_ms(pairs):
+    return [a.elapsed_time(b) for a, b in pairs]
+
+
+def bench_block_step(tr, wl, steps, warmup):
+    import torch
+    cfg = wl.CONFIGS["cfg2_block"]
+    qb, kb, vb = wl.make_qkv_bits(cfg)
+    q, k, v = _dev(qb), _dev(kb), _dev(vb)
+    B, H, S, D = cfg.B, cfg.Hq, cfg.S, cfg.D
+    blk_o = torch.empty((B, H, S, D), dtype=torch.bfloat16, device="cuda")
+    blk_l = torch.empty((B, H, S), dtype=torch.float32, device="cuda")
+    acc_o = torch.zeros((B, H, S, D), dtype=torch.float32, device="cuda")
+    acc_l = torch.full((B, H, S), float("-inf"), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None):
+        if ev is not None:
+            ev[0].record(stream)
+        tr.tr_block_attn(q, k, v, tr.TR_MASK_NONE, cfg.scale, blk_o, blk_l, stream)
+        if ev is not None:
+            ev[1].record(stream)
+        tr.tr_merge(acc_o, acc_l, blk_o, blk_l, stream)
+        if ev is not None:
+            ev[2].record(stream)
+
+    for _ in range(warmup):
+        step()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    attn_ms = _event_ms([(e[0], e[1]) for e in events])
+    merge_ms = _event_ms([(e[1], e[2]) for e in events])
+    attn_avg, merge_avg = sum(attn_ms) / steps, sum(merge_ms) / steps
+    flops = 4.0 * S * S * D * H * B                              # algorithmic: 4*D per (q,k) pair
+    merge_bytes = B * H * S * (D * (4 + 2 + 4) + 3 * 4)          # read acc fp32 + block bf16, write acc; 3 lse words
+    return {
+        "cfg": cfg, "ms_per_step": ms_per_step, "flops": flops,
+        "attn_ms_avg": attn_avg, "attn_ms_min": min(attn_ms), "merge_ms_avg": merge_avg,
+        "attn_tflops": flops / (attn_avg * 1e-3) / 1e12,
+        "merge_gbs": merge_bytes / (merge_avg * 1e-3) / 1e9, "merge_bytes": merge_bytes,
+    }
+
+
+def bench_block_diag(tr, wl, steps, warmup):
+    """The diagonal-causal variant of the block step (half the pairs)."""
+    import torch
+    cfg = wl.CONFIGS["cfg2_block_diag"]
+    qb, kb, vb = wl.make_qkv_bits(cfg)
+    q, k, v = _dev(qb), _dev(kb), _dev(vb)
+    blk_o = torch.empty((cfg.B, cfg.Hq, cfg.S, cfg.D), dtype=torch.bfloat16, device="cuda")
+    blk_l = torch.empty((cfg.B, cfg.Hq, cfg.S), dtype=torch.float32, device="cuda")
+    for _ in range(warmup):
+        tr.tr_block_attn(q, k, v, tr.TR_MASK_CAUSAL_DIAG, cfg.scale, blk_o, blk_l)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in ev:
+        a.record(); tr.tr_block_attn(q, k, v, tr.TR_MASK_CAUSAL_DIAG, cfg.scale, blk_o, blk_l); b.record()
+    torch.cuda.synchronize()
+    ms = sum(_event_ms(ev)) / steps
+    flops = 2.0 * cfg.S * (cfg.S + 1) * cfg.D * cfg.Hq * cfg.B
+    return {"workload": "cfg2 diagonal-causal block step", "ms": ms, "tflops": flops / (ms * 1e-3) / 1e12,
+            "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+
+
+def bench_merge_only(tr, wl, steps, warmup):
+    """Eight fp32 partials [1,32,32768,128] merged in ring order (device-generated N(0,1) / U(-5,15))."""
+    import torch
+    cfg = wl.CONFIGS["cfg4_merge"]
+    g = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    shape = (cfg.B, cfg.H, cfg.S, cfg.D)
+    outs = [torch.randn(shape, dtype=torch.float32, device="cuda", generator=g) for _ in range(cfg.n_partials)]
+    lses = [torch.rand(shape[:3], dtype=torch.float32, device="cuda", generator=g) * (cfg.lse_hi - cfg.lse_lo) + cfg.lse_lo
+            for _ in range(cfg.n_partials)]
+    acc_o = torch.zeros(shape, dtype=torch.float32, device="cuda")
+    acc_l = torch.full(shape[:3], float("-inf"), dtype=torch.float32, device="cuda")
+    per_call_bytes = 3 * (acc_o.numel() + acc_l.numel()) * 4
+    for _ in range(warmup):
+        tr.tr_merge(acc_o, acc_l, outs[0], lses[0])
+    durations = []
+    for _ in range(steps):
+        acc_o.zero_(); acc_l.fill_(float("-inf"))
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(cfg.n_partials)]
+        for i, (a, b) in enumerate(ev):
+            a.record(); tr.tr_merge(acc_o, acc_l, outs[i], lses[i]); b.record()
+        torch.cuda.synchronize()
+        durations += _event_ms(ev)
+    ms = sum(durations) / len(durations)
+    gbs = per_call_bytes / (ms * 1e-3) / 1e9
+    return {"workload": "cfg4 merge-only: 8 fp32 partials [1,32,32768,128] in ring order", "ms_per_merge": ms,
+            "bytes_per_merge": per_call_bytes, "gbs": gbs, "frac_hbm_peak": gbs / PEAK_HBM_GBS}
+
+
+def bench_ring(tr, wl, name, steps, warmup):
+    import torch
+    cfg = wl.CONFIGS[name]
+    g = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    mk = lambda h: (torch.randn((cfg.B, h, cfg.S, cfg.D), dtype=torch.float32, device="cuda", generator=g) * cfg.std).to(torch.bfloat16)
+    q, k, v = mk(cfg.Hq), mk(cfg.Hkv), mk(cfg.Hkv)
+    out = torch.empty((cfg.B, cfg.Hq, cfg.S, cfg.D), dtype=torch.float32, device="cuda")
+    lse = torch.empty((cfg.B, cfg.Hq, cfg.S), dtype=torch.float32, device="cuda")
+    ws = torch.empty(tr.tr_ring_attn_workspace_bytes(q, cfg.n_chunks), dtype=torch.uint8, device="cuda")
+    for _ in range(warmup):
+        tr.tr_ring_attn(q, k, v, cfg.n_chunks, cfg.causal, out, lse, cfg.scale, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        tr.tr_ring_attn(q, k, v, cfg.n_chunks, cfg.causal, out, lse, cfg.scale, ws)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    n, C = cfg.n_chunks, cfg.chunk
+    full_steps = n * (n - 1) // 2 if cfg.causal else n * n
+    diag_steps = n if cfg.causal else 0
+    flops = cfg.B * cfg.Hq * cfg.D * (4.0 * C * C * full_steps + 2.0 * C * (C + 1) * diag_steps)
+    return {"workload": f"{name}: S={cfg.S} as {n} chunks, Hq={cfg.Hq}, Hkv={cfg.Hkv}, causal={cfg.causal}",
+            "block_steps": full_steps + diag_steps, "ms": ms, "tflops": flops / (ms * 1e-3) / 1e12,
+            "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+
+
+def cpu_baseline(wl, budget_s=20.0):
+    """The fp64 oracle on heads of the same block step, on this machine's host cores."""
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    cfg = wl.CONFIGS["cfg2_block"]
+    qb, kb, vb = wl.make_qkv_bits(cfg)
+    f = wl.bf16_bits_to_f64
+    heads, t_used = 0, 0.0
+    while heads < cfg.Hq and (heads == 0 or t_used * (heads + 1) / heads < budget_s):
+        h = heads
+        t0 = time.perf_counter()
+        oracle.attention_block(f(qb[:, h:h + 1]), f(kb[:, h:h + 1]), f(vb[:, h:h + 1]), cfg.scale)
+        t_used += time.perf_counter() - t0
+        heads += 1
+    flops = 4.0 * cfg.S * cfg.S * cfg.D * heads
+    return {"value": flops / t_used / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{heads} of {cfg.Hq} heads of the 4096x4096 D=128 block step, fp64 numpy, {t_used:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-extras", action="store_true", help="skip the merge-only and ring workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2412_20501_amd as tr
+    import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    tr.raw_lib()   # fails loudly if libtokenring.so is missing
+
+    r = bench_block_step(tr, wl, args.steps, args.warmup)
+    cfg = r["cfg"]
+    value = r["flops"] / (r["ms_per_step"] * 1e-3) / 1e12
+    line = {
+        "metric": "block-attn TFLOP/s (one Algorithm-1 iteration: block attention + lse merge)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg2 block step: B1 H32 Sq4096 x Sk4096 D128 bf16 N(0,1), non-causal, "
+                               "bf16 block_out + fp32 block_lse merged into fp32 accumulators",
+                   "seed": cfg.seed, "scale": cfg.scale},
+        "roofline": {"bound": "mfma", "kernel": "block_attn_kernel<128,bf16 out>", "achieved": r["attn_tflops"],
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": r["attn_tflops"] / PEAK_BF16_TFLOPS,
+                     "traffic": None, "ms_avg": r["attn_ms_avg"], "ms_min": r["attn_ms_min"],
+                     "flops_per_launch": r["flops"]},
+        "merge_roofline": {"bound": "hbm", "kernel": "merge_kernel<bf16 block>", "achieved": r["merge_gbs"],
+                           "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": r["merge_gbs"] / PEAK_HBM_GBS,
+                           "traffic": None, "ms_avg": r["merge_ms_avg"], "bytes_per_launch": r["merge_bytes"]},
+    }
+    if not args.no_extras:
+        ex_steps = max(3, min(args.steps, 10))
+        line["extras"] = {
+            "block_diag": bench_block_diag(tr, wl, ex_steps, 2),
+            "merge_only": bench_merge_only(tr, wl, 3, 1),
+            "ring_cfg3": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1),
+            "ring_cfg5": bench_ring(tr, wl, "cfg5_gqa", 2, 1),
+        }
+        torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
