@@ -184,6 +184,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-extras", action="store_true", help="skip the merge-only and ring workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (untimed) so that HBM-traffic counters of a "
+                         "profiler run can be scaled by what they read for a copy of known size")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
@@ -197,6 +200,14 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     tr.raw_lib()   # fails loudly if libtokenring.so is missing
+
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     r = bench_block_step(tr, wl, args.steps, args.warmup)
     cfg = r["cfg"]
