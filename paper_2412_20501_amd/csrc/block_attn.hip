@@ -5,20 +5,26 @@
 // the A operand is a 32-key x 16-d slice of the K tile read from LDS, the B operand a
 // 16-d x 32-query slice of Q^T held in registers for the whole kernel.  In the MFMA
 // accumulator layout lane (q = lane%32, half = lane/32) then owns, for ONE query, the
-// 16 keys {8g + 4*half + r}: the softmax row reductions are in-lane, plus a single
-// cross-half exchange (v_permlane32_swap) for the running max.  The exponentiated tile
-// P^T, rounded to bf16, is already in the B-operand layout of the second product
-// O^T = V^T P^T; its A operand (32 d x 16 keys of V^T) comes from the row-major V tile in
-// LDS through the transposing read ds_read_b64_tr_b16, with the key order inside each
-// 16-key step permuted to match the accumulator layout of P^T (a contraction index may be
-// permuted freely as long as both operands agree).  The O^T accumulator again has one
-// query per lane, so rescaling and the final 1/l need no cross-lane traffic.
+// 16 keys {8g + 4*half + r} of a 32-key sub-tile: the softmax is in-lane.  The
+// exponentiated sub-tile P^T, rounded to bf16, is already in the B-operand layout of the
+// second product O^T = V^T P^T; its A operand (32 d x 16 keys of V^T) comes from the
+// row-major V tile in LDS through the transposing read ds_read_b64_tr_b16, with the key
+// order inside each 16-key step permuted to match the accumulator layout of P^T (a
+// contraction index may be permuted freely as long as both operands agree).  The O^T
+// accumulator again has one query per lane, so rescaling and the final 1/l need no
+// cross-lane traffic.
 //
-// Work split.  A workgroup has 8 waves (two per SIMD, so one wave's softmax VALU work
-// overlaps the other's MFMAs); each wave owns 32 query rows, the workgroup 256.  K/V
-// tiles of 64 keys are staged through double-buffered LDS, the K tile with a 16-byte XOR
-// swizzle and the V tile with a 32-byte XOR swizzle that make the ds_read_b128 and the
-// transposing reads bank-conflict free.
+// Pipeline.  A lone wave issues vector-ALU instructions far below the SIMD's rate and cannot
+// hide its softmax behind another wave's MFMAs, so MFMA and softmax work are interleaved
+// INSIDE every wave, one 32-key sub-tile apart: step j runs, as one instruction stream,
+//     MFMA : O += V_{j-1}^T P_{j-1}      and      S_{j+1} = K_{j+1} Q^T
+//     VALU : P_j = exp2((S_j - m_ref) * scale*log2e), row sums
+// with no dependency between the two halves.  Two such waves per SIMD fill each other's
+// gaps.  A workgroup has 8 waves of 32 query rows (256 rows); K/V tiles of 64 keys (two
+// sub-tiles) go straight from global memory into 4-deep LDS rings (global_load_lds), the K
+// tile with a 16-byte XOR swizzle and the V tile with a 32-byte XOR swizzle that make the
+// ds_read_b128 and the transposing reads bank-conflict free.  One workgroup barrier per
+// 64-key tile hands ring slots over.
 #include <type_traits>
 
 #include "tr_internal.h"
@@ -37,6 +43,7 @@ constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
 constexpr int kBM = kWaves * 32;  // query rows per workgroup
 constexpr int kBN = 64;           // keys per LDS tile
+constexpr int kRing = 4;          // LDS ring depth (tiles) of K and of V
 
 // Exchange between the two 32-lane halves of a wave with v_permlane32_swap, which swaps the
 // upper half of its first operand with the lower half of its second: fed (x, x) it leaves
@@ -114,6 +121,9 @@ __device__ __forceinline__ const __bf16* uniform_ptr(const __bf16* ptr) {
 // ordered by explicit s_waitcnt vmcnt() on the direct-to-LDS loads instead.
 __device__ __forceinline__ void wg_barrier() { __builtin_amdgcn_s_barrier(); }
 
+template <int N>
+using IC = std::integral_constant<int, N>;
+
 template <int D, bool OUT_F32>
 __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p) {
   constexpr int RB = 2 * D;
@@ -123,7 +133,8 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   constexpr int TILE_BYTES = kBN * RB;
   constexpr int RPI = 1024 / RB;           // tile rows one wave-wide 16-byte load instruction covers
   constexpr int IPW = kBN / RPI / kWaves;  // load instructions per wave, tile and tensor
-  constexpr int NS = 3;                    // ring depth of the K and of the V tiles
+  constexpr int NS = kRing;                // ring depth of the K and of the V tiles
+  constexpr int SUB = 32;                  // keys per sub-tile (one MFMA row block)
   static_assert(IPW >= 1, "tile too small for the workgroup");
 
   extern __shared__ __attribute__((aligned(1024))) char lds[];  // K ring | V ring
@@ -131,7 +142,6 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in an SGPR
   const int ql = lane & 31, hf = lane >> 5;
-  const int grp = wave >> 2;  // waves w and w+4 share a SIMD; the two groups run half a period apart
 
   int qt, bh;
   decode_block(p, blockIdx.x, qt, bh);
@@ -148,7 +158,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     for (int ks = 0; ks < KS; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks + 8 * hf);
   }
 
-  // Key range of this workgroup and of this wave.
+  // Key range of this workgroup (in 64-key tiles) and of this wave (in 32-key sub-tiles).
   const int q_last_wg = min(q0 + kBM, p.Sq) - 1;
   int kv_end = p.Sk;
   if (p.causal) kv_end = max(0, min(p.Sk, q_last_wg + p.causal_off + 1));
@@ -158,6 +168,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     wave_kv_end = p.Sk;
     if (p.causal) wave_kv_end = max(0, min(p.Sk, min(qw0 + 31, p.Sq - 1) + p.causal_off + 1));
   }
+  const int jw = (wave_kv_end + SUB - 1) / SUB;  // sub-tiles this wave has visible keys in
 
   const __bf16* kg = p.k + (int64_t)b * p.k_sb + (int64_t)hk * p.k_sh;
   const __bf16* vg = p.v + (int64_t)b * p.v_sb + (int64_t)hk * p.v_sh;
@@ -186,7 +197,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   }
   // Issued as inline asm: the compiler would otherwise treat every later LDS read as possibly
   // aliasing the in-flight load and drain vmcnt to 0 in front of it, serialising the pipeline;
-  // here completion is waited for explicitly, one ring slot ahead of its use.
+  // here completion is waited for explicitly, one tile ahead of the first use.
   const unsigned lds_base = (unsigned)(unsigned long)(lptr_t)lds;
   auto dma16 = [&](const __bf16* base, unsigned off, unsigned lds_off) __attribute__((always_inline)) {
     const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + lds_off);
@@ -209,18 +220,21 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
 
   // Per-lane LDS read offsets.
   // K operand: lane (key = ql, hf) reads chunk 2*ks + hf of row 32*kt + ql.
-  int k_rd[KS];
+  // (All read addresses are LDS byte addresses with the ring base folded in, so that ring
+  // slot and sub-tile offsets are instruction immediates.)
+  unsigned k_rd[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ks++) k_rd[ks] = k_lds_off<D>(ql, 2 * ks + hf);
+  for (int ks = 0; ks < KS; ks++) k_rd[ks] = lds_base + k_lds_off<D>(ql, 2 * ks + hf);
   // V^T operand through the transposing read: within each group of 16 lanes, lane i supplies
   // the address of row (i/4) of the 4-key group, 8-byte segment (i%4) of the 16 d's the
-  // group covers, and receives the 4 keys of d = i.
-  int v_rd[DB];
+  // group covers, and receives the 4 keys of d = i.  (The V ring base is folded in.)
+  unsigned v_rd[DB];
   {
     const int i16 = lane & 15, gq = (lane >> 4) & 1;
     const int row = 4 * hf + (i16 >> 2);
 #pragma unroll
-    for (int db = 0; db < DB; db++) v_rd[db] = NS * TILE_BYTES + v_lds_off<D>(row, 4 * db + 2 * gq) + (i16 & 3) * 8;
+    for (int db = 0; db < DB; db++)
+      v_rd[db] = lds_base + NS * TILE_BYTES + v_lds_off<D>(row, 4 * db + 2 * gq) + (i16 & 3) * 8;
   }
 
   f32x16 o_acc[DB];
@@ -232,124 +246,118 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   float l_run = 0.f;        // this lane's share of the running sum of exp
   const float c2 = p.scale * 1.4426950408889634f;  // scale * log2(e)
 
-  f32x16 s[2];       // S^T of the tile the next softmax consumes
-  bf16x8 pb[2][2];   // P^T of the tile the next PV product consumes
-
-  // The X phase as one software-pipelined MFMA stream.  Operand i is, for i < NPV, the V^T
-  // fragment (kt, t, db) of the PV product (two transposing 64-bit LDS reads) and, for
-  // i >= NPV, the K fragment (ks, kt) of the next tile's QK^T (one 128-bit LDS read).  Reads
-  // run PF operands ahead of the MFMAs that consume them so that LDS latency is covered by
-  // matrix work; sched_group_barrier pins that interleaving in the instruction scheduler.
-  constexpr int NPV = 4 * DB, NQK = 2 * KS, PF = 6;
-  auto load_op = [&](int i, const char* vb, const char* kb) __attribute__((always_inline)) -> bf16x8 {
-    if (i < NPV) {
-      const int kt = i / (2 * DB), t = (i / DB) % 2, db = i % DB;
-      const char* vp = vb + (32 * kt + 16 * t) * RB + v_rd[db];
-      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(vp));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(vp + 8 * RB));
-      const bf16x4 lo_b = __builtin_bit_cast(bf16x4, lo), hi_b = __builtin_bit_cast(bf16x4, hi);
-      return __builtin_shufflevector(lo_b, hi_b, 0, 1, 2, 3, 4, 5, 6, 7);
-    }
-    const int j = i - NPV, ks = j / 2, kt = j % 2;
-    return *reinterpret_cast<const bf16x8*>(kb + kt * 32 * RB + k_rd[ks]);
-  };
-  auto do_mfma = [&](int i, bf16x8 a) __attribute__((always_inline)) {
-    if (i < NPV) {
-      const int kt = i / (2 * DB), t = (i / DB) % 2, db = i % DB;
-      o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kt][t], o_acc[db], 0, 0, 0);
-    } else {
-      const int j = i - NPV, ks = j / 2, kt = j % 2;
-      s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kt], 0, 0, 0);
-    }
-  };
-  // ops [first, last) of the stream: PV only, QK only, or both back to back
-  auto mfma_stream = [&](auto first_c, auto last_c, auto v_slot_c, auto k_slot_c) __attribute__((always_inline)) {
-    constexpr int first = decltype(first_c)::value, last = decltype(last_c)::value;
-    // ring slots are compile-time so that every LDS read offset is an instruction immediate
-    const char* vb = lds + decltype(v_slot_c)::value * TILE_BYTES;  // v_rd already includes the V ring base
-    const char* kb = lds + decltype(k_slot_c)::value * TILE_BYTES;
-    if (last > NPV) {
-#pragma unroll
-      for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-        for (int i = 0; i < 16; i++) s[kt][i] = 0.f;
-    }
-    bf16x8 ops[NPV + NQK];
-#pragma unroll
-    for (int i = first; i < first + PF && i < last; i++) ops[i] = load_op(i, vb, kb);
-#pragma unroll
-    for (int i = first; i < last; i++) {
-      if (i + PF < last) ops[i + PF] = load_op(i + PF, vb, kb);
-      do_mfma(i, ops[i]);
-    }
-    // scheduling pipeline: prologue reads, then per MFMA the reads issued PF operands ahead
-#pragma unroll
-    for (int i = first; i < first + PF && i < last; i++) {
-      if (i < NPV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-#pragma unroll
-    for (int i = first; i < last; i++) {
-      if (i + PF < last) {
-        if (i + PF < NPV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    }
-  };
-  using std::integral_constant;
-  using C0 = integral_constant<int, 0>;
-  auto qk = [&](auto k_slot_c) __attribute__((always_inline)) { mfma_stream(integral_constant<int, NPV>{}, integral_constant<int, NPV + NQK>{}, C0{}, k_slot_c); };
-  auto pv_qk = [&](auto v_slot_c, auto k_slot_c) __attribute__((always_inline)) {
-    mfma_stream(C0{}, integral_constant<int, NPV + NQK>{}, v_slot_c, k_slot_c);
-  };
-  // Online softmax of s (tile starting at key kstart): fills pb, updates m_ref, l_run, O.
+  // ---- one step ---------------------------------------------------------------------
+  // Step j (sub-tile j starts at key kstart) runs, as ONE interleaved instruction stream,
+  //   MFMA : S_{j+1} = K_{j+1} Q^T   (NQK MFMAs, operands read from LDS by the PREVIOUS step)
+  //          O += V_{j-1}^T P_{j-1}^T (NPV MFMAs, operands read from LDS during the QK half)
+  //   LDS  : while the PV half runs, the K operands of step j+1 are read (into `pre`), so the
+  //          read stream never stops at a step boundary or at a barrier (the tile they come
+  //          from became visible a whole tile earlier)
+  //   VALU : P_j = exp2((S_j - m_ref) * c2) and its row sums
+  // QK goes first so that S_{j+1} is complete long before the next step's softmax reads it.
+  //
   // P = exp2((s - m_ref) * scale*log2e) with an exponent reference m_ref that is NOT the
   // running maximum: any reference gives the same out = O/l and lse = m_ref*scale + ln l, so
-  // the common path takes no row maximum at all.  It exponentiates against the current
-  // reference and sums; since P >= 0, a tile sum <= kSumCap bounds every P of the tile.  Only
-  // if some lane's sum exceeds the cap (or is NaN from inf - inf), or the reference is still
-  // -inf, the slow path runs: take the row maximum, raise the reference, rescale l and the
-  // O accumulators, and redo the exponentials.  Row sums use the unrounded fp32 P: summing
-  // the bf16-rounded weights would cost up to 2^-9 relative in l, more than the 1e-3 budget of
-  // lse for rows that see only a few keys.
+  // the common path takes no row maximum.  Since P >= 0, a sub-tile sum <= kSumCap bounds
+  // every P.  Only if some lane's sum exceeds the cap (or is NaN), or the reference is still
+  // -inf, the slow path runs after the stream: row maximum, raise the reference, rescale l
+  // and the O accumulators (which by then include P_{j-1}, consistently), redo the exponentials.
+  // Row sums use the unrounded fp32 P: summing the bf16-rounded weights would cost up to
+  // 2^-9 relative in l, more than the 1e-3 budget of lse for rows that see only a few keys.
+  //
+  // The stream is written out in the order it should issue - per MFMA: one operand's LDS
+  // reads, the MFMA, and a slice of the softmax whose three dependent stages (fma, exp2,
+  // add/convert) are staggered across consecutive slices - and pinned with sched_barrier.
+  constexpr int NPV = 2 * DB, NQK = KS;
+  static_assert(NPV == NQK, "the two halves of a step carry the same number of MFMAs");
+  typedef const s16x4 __attribute__((address_space(3)))* lds_tr_ptr;
+  typedef const bf16x8 __attribute__((address_space(3)))* lds_b128_ptr;
+  auto load_k = [&](int ks, unsigned k_imm) __attribute__((always_inline)) -> bf16x8 {
+    return *(lds_b128_ptr)(unsigned long)(k_rd[ks] + k_imm);
+  };
+  auto load_v = [&](int i, unsigned v_imm) __attribute__((always_inline)) -> bf16x8 {
+    const int t = i / DB, db = i % DB;
+    const unsigned a = v_rd[db] + v_imm + 16 * t * RB;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(lds_tr_ptr)(unsigned long)a);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(lds_tr_ptr)(unsigned long)(a + 8 * RB));
+    const bf16x4 lo_b = __builtin_bit_cast(bf16x4, lo), hi_b = __builtin_bit_cast(bf16x4, hi);
+    return __builtin_shufflevector(lo_b, hi_b, 0, 1, 2, 3, 4, 5, 6, 7);
+  };
+  bf16x8 pre[NQK];  // K operands of the next step's QK half, read one step ahead
+
   constexpr float kSumCap = 65536.f;
-  auto softmax = [&](int kstart) __attribute__((always_inline)) {
-    const bool need_mask = (kstart + kBN > p.Sk) || (p.causal && (kstart + kBN - 1 > qw0 + p.causal_off));
+  auto step = [&](int kstart, auto first_c, auto v_imm_c, auto k_imm_next_c, f32x16& s_in, f32x16& s_out,
+                  bf16x8 (&p_in)[2], bf16x8 (&p_out)[2]) __attribute__((always_inline)) {
+    constexpr bool FIRST = decltype(first_c)::value != 0;   // no previous sub-tile: QK half only
+    constexpr int n_mfma = FIRST ? NQK : NQK + NPV;
+    constexpr int EPM = 16 / n_mfma;  // softmax elements handled per MFMA slice
+    static_assert(16 % n_mfma == 0, "softmax elements must divide evenly over the MFMAs");
+    constexpr unsigned v_imm = decltype(v_imm_c)::value, k_imm_next = decltype(k_imm_next_c)::value;
+
+    const bool need_mask = (kstart + SUB > p.Sk) || (p.causal && (kstart + SUB - 1 > qw0 + p.causal_off));
     if (need_mask) {
       int limit = p.Sk - 1;
       if (p.causal) limit = min(limit, qrow + p.causal_off);
 #pragma unroll
-      for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-        for (int i = 0; i < 16; i++) {
-          const int key = kstart + 32 * kt + 8 * (i >> 2) + 4 * hf + (i & 3);
-          if (key > limit) s[kt][i] = -INFINITY;
-        }
+      for (int i = 0; i < 16; i++) {
+        const int key = kstart + 8 * (i >> 2) + 4 * hf + (i & 3);
+        if (key > limit) s_in[i] = -INFINITY;
+      }
     }
-    auto exp_tile = [&]() __attribute__((always_inline)) -> float {
-      const float mc = (m_ref == -INFINITY) ? 0.f : m_ref * c2;
-      float ps0 = 0.f, ps1 = 0.f;
+
+    const float mc = (m_ref == -INFINITY) ? 0.f : m_ref * c2;
+    f32x16 acc;
 #pragma unroll
-      for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-        for (int i = 0; i < 16; i += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][i], c2, -mc));
-          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][i + 1], c2, -mc));
-          pb[kt][i >> 3][i & 7] = (__bf16)p0;
-          pb[kt][i >> 3][(i & 7) + 1] = (__bf16)p1;
-          ps0 += p0;
-          ps1 += p1;
-        }
-      return ps0 + ps1;
+    for (int i = 0; i < 16; i++) acc[i] = 0.f;
+    bf16x8 pv_ops[NPV], nxt[NQK];
+    float tq[16], ex[16];
+    float ps0 = 0.f, ps1 = 0.f;
+    // softmax element e passes stage A (fma) in slice e/EPM, stage B (exp2) one slice later and
+    // stage C (sum, convert) two slices later; the last two slices' leftovers drain after the loop
+    auto stage_a = [&](int e) __attribute__((always_inline)) { tq[e] = __builtin_fmaf(s_in[e], c2, -mc); };
+    auto stage_b = [&](int e) __attribute__((always_inline)) { ex[e] = __builtin_amdgcn_exp2f(tq[e]); };
+    auto stage_c = [&](int e) __attribute__((always_inline)) {
+      if (e & 1) {
+        ps1 += ex[e];
+        p_out[e >> 3][(e & 7) - 1] = (__bf16)ex[e - 1];
+        p_out[e >> 3][e & 7] = (__bf16)ex[e];
+      } else {
+        ps0 += ex[e];
+      }
     };
-    float psum = exp_tile();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < n_mfma; i++) {
+      if (i < NQK) {
+        if (FIRST) nxt[i] = load_k(i, k_imm_next);
+        else pv_ops[i] = load_v(i, v_imm);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pre[i], qf[i], acc, 0, 0, 0);
+      } else {
+        const int j = i - NQK;
+        nxt[j] = load_k(j, k_imm_next);
+        o_acc[j % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pv_ops[j], p_in[j / DB], o_acc[j % DB], 0, 0, 0);
+      }
+#pragma unroll
+      for (int k = 0; k < EPM; k++) {
+        stage_a(i * EPM + k);
+        if (i >= 1) stage_b((i - 1) * EPM + k);
+        if (i >= 2) stage_c((i - 2) * EPM + k);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int k = 0; k < EPM; k++) {
+      stage_b((n_mfma - 1) * EPM + k);
+      stage_c((n_mfma - 2) * EPM + k);
+    }
+#pragma unroll
+    for (int k = 0; k < EPM; k++) stage_c((n_mfma - 1) * EPM + k);
+    float psum = ps0 + ps1;
+
     if (__any(!(psum <= kSumCap) || m_ref == -INFINITY)) {
-      float tmax = s[0][0];
+      float tmax = s_in[0];
 #pragma unroll
-      for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-        for (int i = 0; i < 16; i++) tmax = fmaxf(tmax, s[kt][i]);
+      for (int i = 1; i < 16; i++) tmax = fmaxf(tmax, s_in[i]);
       tmax = half_swap_max(tmax);
       const float m_new = fmaxf(m_ref, tmax);
       const float alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * c2);  // m_ref = -inf -> 0; equal -> 1
@@ -360,12 +368,26 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
 #pragma unroll
         for (int i = 0; i < 16; i++) o_acc[db][i] *= a;
       m_ref = m_new;
-      psum = exp_tile();
+      const float mc2 = (m_ref == -INFINITY) ? 0.f : m_ref * c2;
+      float q0s = 0.f, q1s = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_in[i], c2, -mc2));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_in[i + 1], c2, -mc2));
+        p_out[i >> 3][i & 7] = (__bf16)p0;
+        p_out[i >> 3][(i & 7) + 1] = (__bf16)p1;
+        q0s += p0;
+        q1s += p1;
+      }
+      psum = q0s + q1s;
     }
     l_run += psum;
+    s_out = acc;
+#pragma unroll
+    for (int i = 0; i < NQK; i++) pre[i] = nxt[i];
   };
 
-  // ---- prologue: K_0, K_1, K_2, V_0, V_1 into the rings; S_0 = K_0 Q^T
+  // ---- prologue: K_0..K_2, V_0, V_1 into the rings
   if (n_tiles > 0) {
     issue_k(0, 0);
     issue_v(0, 0);
@@ -376,47 +398,58 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
 #pragma unroll
   for (int ks = 0; ks < KS; ks++) asm volatile("" ::"v"(qf[ks]));  // Q is in registers before the loop
   __builtin_amdgcn_s_waitcnt(0);
-  wg_barrier();
-  if (0 < wave_kv_end) qk(C0{});
-  if (grp == 1) wg_barrier();  // group 1 runs one phase behind group 0
+  wg_barrier();  // B_0
 
-  // Steady state, two phases per tile separated by workgroup barriers:
-  //   Y(u): softmax of S_u (VALU)            X(u): O += V_u P_u, then S_{u+1} = K_{u+1} Q^T (MFMA)
-  // Group 0 is in X while group 1 is in Y and vice versa, so each SIMD always has one wave
-  // feeding the MFMA pipe and one doing VALU work.  At the start of group 0's X(u) (= group
-  // 1's Y(u)) every wave issues the loads of K_{u+3} and V_{u+2} into the ring slots that
-  // K_u and V_{u-1} just vacated; they are waited for (in order, all but the newest 2*IPW)
-  // right before the barrier that precedes their first use two tiles later.
-  auto tile_step = [&](int u, auto vs_c) __attribute__((always_inline)) {   // vs_c = u % NS: ring slot of V_u; K_{u+1} sits in the next one
-    constexpr int vs = decltype(vs_c)::value, ks = (vs + 1) % NS;
-    constexpr int ld_k_slot = vs, ld_v_slot = (vs + 2) % NS;  // slots of K_{u+3} (was K_u) and V_{u+2} (was V_{u-1})
-    const bool act = u * kBN < wave_kv_end;
-    // ---- Y(u)
-    if (grp == 1) {
-      issue_k(u + 3, ld_k_slot);
-      issue_v(u + 2, ld_v_slot);
+  // Ring protocol.  Sub-tile j = 2u + kt lives in tile u.  K_u is read in steps 2u-2 .. 2u
+  // (step 2u-2 only prefetches), V_u in steps 2u+1 and 2u+2.  Barrier B_u sits in front of
+  // step 2u.  Right after B_w every wave issues the loads of K_{w+3} and V_{w+2} into the
+  // slots K_{w-1} and V_{w-2} vacated (all waves are past step 2w-1); they are first read in
+  // step 2w+4, so each wave waits for its share (all but the newest 2*IPW loads, in order)
+  // right before B_{w+2}.
+  // S and P alternate between two register sets: even steps read sA / pB and write sB / pA,
+  // odd steps the other way round, so no step has to copy its results.
+  f32x16 sA, sB;
+  bf16x8 pA[2], pB[2];
+  constexpr unsigned kKt1 = SUB * RB;  // byte offset of the second sub-tile inside a tile
+  if (n_tiles > 0) {
+    issue_k(3, 3 % NS);
+    issue_v(2, 2 % NS);
+    if (jw > 0) {
+      // S_0 = K_0[0:32] Q^T, plain (nothing to overlap with yet); operands of step 0 (K_0, kt 1)
+#pragma unroll
+      for (int i = 0; i < 16; i++) sA[i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++) sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_k(ks, 0), qf[ks], sA, 0, 0, 0);
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++) pre[ks] = load_k(ks, kKt1);
+      // step 0: S_1 from (K_0, kt 1) alongside the softmax of sub-tile 0; prefetch (K_1, kt 0)
+      step(0, IC<1>{}, IC<0>{}, IC<1 * TILE_BYTES>{}, sA, sB, pB, pA);
+      // step 1: PV of sub-tile 0 (V_0, kt 0), S_2 from (K_1, kt 0), softmax of sub-tile 1; prefetch (K_1, kt 1)
+      if (1 <= jw) step(SUB, IC<0>{}, IC<0>{}, IC<1 * TILE_BYTES + kKt1>{}, sB, sA, pA, pB);
     }
-    if (act) softmax(u * kBN);
-    if (grp == 0) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * IPW) /* vmcnt only */);
-    wg_barrier();
-    // ---- X(u)
-    if (grp == 0) {
-      issue_k(u + 3, ld_k_slot);
-      issue_v(u + 2, ld_v_slot);
-    }
-    // One code path only: when tile u+1 is not needed by this wave (or does not exist) the QK
-    // half still runs on whatever the ring slot holds and its result is never used.  Separate
-    // PV-only / PV+QK branches would make the compiler keep two copies of the O accumulators.
-    if (act) pv_qk(integral_constant<int, vs>{}, integral_constant<int, ks>{});
-    if (grp == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * IPW));
-    wg_barrier();
-  };
-  for (int u = 0; u < n_tiles; u += NS) {
-    tile_step(u, integral_constant<int, 0>{});
-    if (u + 1 < n_tiles) tile_step(u + 1, integral_constant<int, 1>{});
-    if (u + 2 < n_tiles) tile_step(u + 2, integral_constant<int, 2>{});
   }
-  if (grp == 0) wg_barrier();
+  // tiles u = 1 .. n_tiles: steps 2u and 2u+1 (the last tile index only has step 2u, which
+  // folds in the PV product of the final sub-tile; its softmax sees only masked keys)
+  auto tile_body = [&](int u, auto slot_c) __attribute__((always_inline)) {   // slot_c = u % NS
+    constexpr int su = decltype(slot_c)::value, sp = (su + NS - 1) % NS, sn = (su + 1) % NS;
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * IPW));  // vmcnt only
+    wg_barrier();                                    // B_u
+    issue_k(u + 3, (su + 3) % NS);
+    issue_v(u + 2, (su + 2) % NS);
+    // step 2u: S of sub-tile 2u+1 (K_u, kt 1, already in `pre`); PV of sub-tile 2u-1 (V_{u-1}, kt 1);
+    //          softmax of sub-tile 2u; prefetch (K_{u+1}, kt 0)
+    if (2 * u <= jw) step(2 * u * SUB, IC<0>{}, IC<sp * TILE_BYTES + kKt1>{}, IC<sn * TILE_BYTES>{}, sA, sB, pB, pA);
+    // step 2u+1: S of sub-tile 2u+2 (K_{u+1}, kt 0); PV of sub-tile 2u (V_u, kt 0);
+    //          softmax of sub-tile 2u+1; prefetch (K_{u+1}, kt 1)
+    if (u < n_tiles && 2 * u + 1 <= jw)
+      step((2 * u + 1) * SUB, IC<0>{}, IC<su * TILE_BYTES>{}, IC<sn * TILE_BYTES + kKt1>{}, sB, sA, pA, pB);
+  };
+  for (int u0 = 0; u0 <= n_tiles; u0 += NS) {
+    if (u0 >= 1) tile_body(u0, IC<0>{});
+    if (u0 + 1 <= n_tiles) tile_body(u0 + 1, IC<1 % NS>{});
+    if (u0 + 2 <= n_tiles) tile_body(u0 + 2, IC<2 % NS>{});
+    if (u0 + 3 <= n_tiles) tile_body(u0 + 3, IC<3 % NS>{});
+  }
   __builtin_amdgcn_s_waitcnt(0);  // no LDS write of this workgroup may still be in flight at exit
 
   // ---- epilogue: normalise, write block_out and block_lse
@@ -450,7 +483,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
 
 template <int D, bool OUT_F32>
 hipError_t launch_one(const AttnParams& p, dim3 grid, hipStream_t stream) {
-  constexpr int lds_bytes = 2 * 3 * kBN * 2 * D;
+  constexpr int lds_bytes = 2 * kRing * kBN * 2 * D;
   static bool attr_set = false;  // raising the dynamic-LDS limit is a per-function, per-process setting
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&block_attn_kernel<D, OUT_F32>),
