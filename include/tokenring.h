@@ -90,6 +90,18 @@ tr_status tr_block_attn_causal_at(const tr_tensor* q, const tr_tensor* k, const 
                                   const tr_tensor* out, const tr_tensor* lse, void* hip_stream);
 
 /*
+ * Block step fused with the Update (Algorithm 1's Attention followed by Update, Sec. 3.1-3.2):
+ * the block result is never written out; the kernel's epilogue merges it straight into the
+ * fp32 accumulators, exactly as tr_merge would (same arithmetic, same identity handling).
+ *   q [B,Hq,Sq,D] bf16   k, v [B,Hkv,Sk,D] bf16   D in {64, 128}
+ *   out_acc [B,Hq,Sq,D] fp32 (read + written)   lse_acc [B,Hq,Sq] fp32 (read + written)
+ * Rows whose lse_acc is -inf are treated as empty: their out_acc need not be initialised.
+ */
+tr_status tr_block_attn_merge(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v,
+                              int mask_kind, float scale,
+                              const tr_tensor* out_acc, const tr_tensor* lse_acc, void* hip_stream);
+
+/*
  * Out, Lse <- Update(block_out, block_lse), the two equations of Sec. 3.1, in place:
  *   out_acc <- out_acc - sigmoid(block_lse - lse_acc) * (out_acc - block_out)
  *   lse_acc <- lse_acc - ln(sigmoid(lse_acc - block_lse))
@@ -111,19 +123,22 @@ tr_status tr_merge(const tr_tensor* out_acc, const tr_tensor* lse_acc,
  * steps with j > c are skipped and j == c uses the diagonal mask.
  *   q [B,Hq,S,D] bf16   k, v [B,Hkv,S,D] bf16   out [B,Hq,S,D] fp32   lse [B,Hq,S] fp32
  *   S must be a multiple of n_chunks; n_chunks >= 1; scale <= 0 selects 1/sqrt(D).
- *   workspace: device memory of at least tr_ring_attn_workspace_bytes(q, n_chunks) bytes,
- *   256-byte aligned, holding one fp32 block result (block_out, block_lse) between the
- *   attention step and its merge.  Its contents on return are unspecified.
- * The first block of every Query chunk is written straight into out/lse, so the caller
- * need not initialise them.  All launches go to `hip_stream` in a fixed order, hence the
- * result is bitwise reproducible.
+ *   workspace == NULL (workspace_bytes ignored): every step after a Query chunk's first one
+ *   runs as tr_block_attn_merge, i.e. the Update happens in the attention kernel's epilogue.
+ *   workspace != NULL: the two-kernel form of Algorithm 1 - tr_block_attn writes one fp32
+ *   block result (block_out, block_lse) into the workspace and tr_merge folds it into
+ *   out/lse.  It needs at least tr_ring_attn_workspace_bytes(q, n_chunks) bytes, 256-byte
+ *   aligned; its contents on return are unspecified.
+ * Both forms apply the same Update arithmetic in the same order.  The first block of every
+ * Query chunk is written straight into out/lse, so the caller need not initialise them.  All
+ * launches go to `hip_stream` in a fixed order, hence the result is bitwise reproducible.
  */
 tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v,
                        int n_chunks, int causal,
                        const tr_tensor* out, const tr_tensor* lse, float scale,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Bytes of workspace tr_ring_attn needs for these shapes (0 on invalid arguments). */
+/* Bytes of workspace the two-kernel form of tr_ring_attn needs for these shapes (0 on invalid arguments). */
 size_t tr_ring_attn_workspace_bytes(const tr_tensor* q, int n_chunks);
 
 /* Description of the last error on the calling thread ("" if none). Static storage. */

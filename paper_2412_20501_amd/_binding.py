@@ -49,6 +49,8 @@ def _load():
     lib.tr_block_attn.restype = ctypes.c_int
     lib.tr_block_attn_causal_at.argtypes = [P, P, P, ctypes.c_int64, ctypes.c_int64, ctypes.c_float, P, P, ctypes.c_void_p]
     lib.tr_block_attn_causal_at.restype = ctypes.c_int
+    lib.tr_block_attn_merge.argtypes = [P, P, P, ctypes.c_int, ctypes.c_float, P, P, ctypes.c_void_p]
+    lib.tr_block_attn_merge.restype = ctypes.c_int
     lib.tr_merge.argtypes = [P, P, P, P, ctypes.c_void_p]
     lib.tr_merge.restype = ctypes.c_int
     lib.tr_ring_attn.argtypes = [P, P, P, ctypes.c_int, ctypes.c_int, P, P, ctypes.c_float,
@@ -118,6 +120,12 @@ def tr_block_attn_causal_at(q, k, v, q_pos0, k_pos0, scale, out, lse, stream=Non
                                         desc(out), desc(lse), _stream(stream)))
 
 
+def tr_block_attn_merge(q, k, v, mask_kind, scale, out_acc, lse_acc, stream=None):
+    """Block step whose epilogue applies the Update to the fp32 accumulators (see tokenring.h)."""
+    _check(_lib.tr_block_attn_merge(desc(q), desc(k), desc(v), int(mask_kind), float(scale), desc(out_acc), desc(lse_acc),
+                                    _stream(stream)))
+
+
 def tr_merge(out_acc, lse_acc, block_out, block_lse, stream=None):
     """Out, Lse <- Update(block_out, block_lse), in place on out_acc / lse_acc."""
     _check(_lib.tr_merge(desc(out_acc), desc(lse_acc), desc(block_out), desc(block_lse), _stream(stream)))
@@ -130,8 +138,9 @@ def tr_ring_attn_workspace_bytes(q, n_chunks) -> int:
 def tr_ring_attn(q, k, v, n_chunks, causal, out, lse, scale=0.0, workspace=None, stream=None):
     """Algorithm 1's schedule on one GPU into fp32 `out`, `lse`.
 
-    `workspace` is a caller-owned uint8 device tensor of at least
-    tr_ring_attn_workspace_bytes(q, n_chunks) bytes (needed when n_chunks > 1).
+    `workspace` = None: the Update runs fused in the attention epilogue.  Otherwise a
+    caller-owned uint8 device tensor of at least tr_ring_attn_workspace_bytes(q, n_chunks)
+    bytes selects the two-kernel form (tr_block_attn into the workspace, then tr_merge).
     """
     ws_ptr, ws_bytes = None, 0
     if workspace is not None:

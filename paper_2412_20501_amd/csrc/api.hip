@@ -59,13 +59,14 @@ tr_status check_tensor(const char* name, const tr_tensor* t, bool allow_bf16, bo
   return TR_OK;
 }
 
+// fuse_update: out/lse are fp32 accumulators and the block is merged into them by the kernel's epilogue
 tr_status attn_common(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int causal, int64_t off64, float scale,
-                      const tr_tensor* out, const tr_tensor* lse, void* stream) {
+                      const tr_tensor* out, const tr_tensor* lse, void* stream, bool fuse_update = false) {
   tr_status st;
   if ((st = check_tensor("q", q, true, false, 16)) != TR_OK) return st;
   if ((st = check_tensor("k", k, true, false, 16)) != TR_OK) return st;
   if ((st = check_tensor("v", v, true, false, 16)) != TR_OK) return st;
-  if ((st = check_tensor("out", out, true, true, 16)) != TR_OK) return st;
+  if ((st = check_tensor("out", out, !fuse_update, true, 16)) != TR_OK) return st;
   if ((st = check_tensor("lse", lse, false, true, 4)) != TR_OK) return st;
   if (q->D != 64 && q->D != 128) return fail(TR_ERR_SHAPE, "head dim %lld not supported (64 or 128)", (long long)q->D);
   if (k->D != q->D || v->D != q->D || out->D != q->D) return fail(TR_ERR_SHAPE, "head dims of q, k, v, out differ");
@@ -97,7 +98,8 @@ tr_status attn_common(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v
   p.n_qtiles = (p.Sq + bm - 1) / bm;
   p.xcd_map = (p.B * p.Hkv) % 8 == 0 && (int64_t)p.n_qtiles * p.B * p.Hq >= 8;
   if (p.B == 0 || p.Hq == 0 || p.Sq == 0) return TR_OK;
-  const hipError_t e = tr::launch_block_attn(p, (int)q->D, out->dtype == TR_F32, (hipStream_t)stream);
+  const int epilogue = fuse_update ? 2 : (out->dtype == TR_F32 ? 1 : 0);
+  const hipError_t e = tr::launch_block_attn(p, (int)q->D, epilogue, (hipStream_t)stream);
   if (e != hipSuccess) return fail(TR_ERR_HIP, "block attention launch failed: %s", hipGetErrorString(e));
   return TR_OK;
 }
@@ -134,6 +136,15 @@ tr_status tr_block_attn_causal_at(const tr_tensor* q, const tr_tensor* k, const 
   g_err[0] = 0;
   if (q_pos0 < 0 || k_pos0 < 0) return fail(TR_ERR_SHAPE, "chunk positions must be >= 0");
   return attn_common(q, k, v, 1, q_pos0 - k_pos0, scale, out, lse, hip_stream);
+}
+
+tr_status tr_block_attn_merge(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int mask_kind, float scale,
+                              const tr_tensor* out_acc, const tr_tensor* lse_acc, void* hip_stream) {
+  g_err[0] = 0;
+  if (mask_kind != TR_MASK_NONE && mask_kind != TR_MASK_CAUSAL_DIAG) return fail(TR_ERR_UNSUPPORTED, "unknown mask kind %d", mask_kind);
+  if (mask_kind == TR_MASK_CAUSAL_DIAG && q && k && q->S != k->S)
+    return fail(TR_ERR_SHAPE, "the diagonal causal mask needs Sq == Sk (got %lld, %lld)", (long long)q->S, (long long)k->S);
+  return attn_common(q, k, v, mask_kind == TR_MASK_CAUSAL_DIAG, 0, scale, out_acc, lse_acc, hip_stream, true);
 }
 
 tr_status tr_merge(const tr_tensor* out_acc, const tr_tensor* lse_acc, const tr_tensor* block_out, const tr_tensor* block_lse,
@@ -209,8 +220,9 @@ tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* 
   const size_t rows = (size_t)q->B * (size_t)q->H * (size_t)C;
   tr_tensor ws_out, ws_lse;
   memset(&ws_out, 0, sizeof(ws_out));
-  if (n_chunks > 1 && rows > 0) {
-    if (!workspace) return fail(TR_ERR_WORKSPACE, "workspace is NULL (need %zu bytes)", need);
+  const bool fused = workspace == nullptr;  // no workspace: the Update runs in the attention epilogue
+  if (!fused && workspace_bytes == 0) return fail(TR_ERR_WORKSPACE, "workspace given with size 0 (need %zu bytes)", need);
+  if (!fused && n_chunks > 1 && rows > 0) {
     if (((uintptr_t)workspace) % kWsAlign) return fail(TR_ERR_WORKSPACE, "workspace must be %zu-byte aligned", kWsAlign);
     if (workspace_bytes < need) return fail(TR_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, need);
     ws_out.ptr = workspace; ws_out.dtype = TR_F32;
@@ -236,6 +248,9 @@ tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* 
       if (i == 0) {
         // first block of Query chunk c: it *is* the accumulator's initial value
         st = attn_common(&qc, &kj, &vj, diag, 0, scale, &oc, &lc, hip_stream);
+        if (st != TR_OK) return st;
+      } else if (fused) {
+        st = attn_common(&qc, &kj, &vj, diag, 0, scale, &oc, &lc, hip_stream, true);
         if (st != TR_OK) return st;
       } else {
         st = attn_common(&qc, &kj, &vj, diag, 0, scale, &ws_out, &ws_lse, hip_stream);

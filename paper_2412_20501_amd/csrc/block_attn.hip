@@ -44,6 +44,7 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kBM = kWaves * 32;  // query rows per workgroup
 constexpr int kBN = 64;           // keys per LDS tile
 constexpr int kRing = 4;          // LDS ring depth (tiles) of K and of V
+constexpr int kEpiBf16 = 0, kEpiF32 = 1, kEpiMerge = 2;
 
 // Exchange between the two 32-lane halves of a wave with v_permlane32_swap, which swaps the
 // upper half of its first operand with the lower half of its second: fed (x, x) it leaves
@@ -124,7 +125,9 @@ __device__ __forceinline__ void wg_barrier() { __builtin_amdgcn_s_barrier(); }
 template <int N>
 using IC = std::integral_constant<int, N>;
 
-template <int D, bool OUT_F32>
+// EPI selects the epilogue: kEpiBf16 / kEpiF32 store block_out and block_lse; kEpiMerge folds
+// the block straight into fp32 accumulators with the Update of Sec. 3.1 (no block_out round trip).
+template <int D, int EPI>
 __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p) {
   constexpr int RB = 2 * D;
   constexpr int KS = D / 16;               // MFMA k-steps over the head dim
@@ -452,57 +455,97 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   }
   __builtin_amdgcn_s_waitcnt(0);  // no LDS write of this workgroup may still be in flight at exit
 
-  // ---- epilogue: normalise, write block_out and block_lse
+  // ---- epilogue: normalise, then store (or merge) with fully coalesced global accesses.
+  // In the accumulator layout a lane holds 4-float pieces of ONE row, 32 bytes apart from its
+  // neighbour's; each wave therefore transposes its 32 x D tile through a private, chunk-
+  // swizzled LDS region (the rings are dead by now) and reads it back row-major, one 16-byte
+  // chunk per lane, so that every global row is touched as one contiguous segment.
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();  // every wave is done with the K/V rings and none of its loads is still landing
+  constexpr int ROWB = 4 * D;                 // bytes of one fp32 output row
+  constexpr int CPRF = D / 4;                 // 16-byte chunks per fp32 row = lanes per row when reading back
+  constexpr int RPI_OUT = 64 / CPRF;          // rows one wave-wide access covers
+  char* const my = lds + wave * (32 * ROWB);
+  float* const my_lse = reinterpret_cast<float*>(lds + kWaves * 32 * ROWB) + wave * 32;
   const float l_tot = half_swap_sum(l_run);
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-  if (qrow < p.Sq) {
-    if (hf == 0) {
-      const float lse = l_tot > 0.f ? m_ref * p.scale + logf(l_tot) : -INFINITY;
-      p.lse[(int64_t)b * p.l_sb + (int64_t)hq * p.l_sh + (int64_t)qrow * p.l_ss] = lse;
+  const float lse_blk = l_tot > 0.f ? m_ref * p.scale + logf(l_tot) : -INFINITY;
+#pragma unroll
+  for (int db = 0; db < DB; db++)
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      const int c = 8 * db + 2 * g + hf;  // 16-byte chunk of d = 32*db + 8*g + 4*hf
+      f32x4 o;
+#pragma unroll
+      for (int r = 0; r < 4; r++) o[r] = o_acc[db][4 * g + r] * inv;
+      *reinterpret_cast<f32x4*>(my + ql * ROWB + ((c ^ (ql & 15)) << 4)) = o;
     }
-    const int64_t obase = (int64_t)b * p.o_sb + (int64_t)hq * p.o_sh + (int64_t)qrow * p.o_ss;
+  if (hf == 0) my_lse[ql] = lse_blk;
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the wave's own LDS writes are visible to all its lanes
+  if (EPI != kEpiMerge && hf == 0 && qrow < p.Sq)
+    p.lse[(int64_t)b * p.l_sb + (int64_t)hq * p.l_sh + (int64_t)qrow * p.l_ss] = lse_blk;
+  const int rr = lane / CPRF, cc = lane % CPRF;
 #pragma unroll
-    for (int db = 0; db < DB; db++)
+  for (int it = 0; it < 32 / RPI_OUT; it++) {
+    const int r = it * RPI_OUT + rr;
+    const int grow = qw0 + r;
+    const f32x4 o = *reinterpret_cast<const f32x4*>(my + r * ROWB + ((cc ^ (r & 15)) << 4));
+    if (grow < p.Sq) {
+      const int64_t obase = (int64_t)b * p.o_sb + (int64_t)hq * p.o_sh + (int64_t)grow * p.o_ss + 4 * cc;
+      if (EPI == kEpiBf16) {
+        bf16x4 ob;
 #pragma unroll
-      for (int g = 0; g < 4; g++) {
-        const int d0 = 32 * db + 8 * g + 4 * hf;
-        f32x4 o;
-#pragma unroll
-        for (int r = 0; r < 4; r++) o[r] = o_acc[db][4 * g + r] * inv;
-        if (OUT_F32) {
-          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + obase + d0) = o;
-        } else {
-          bf16x4 ob;
-#pragma unroll
-          for (int r = 0; r < 4; r++) ob[r] = (__bf16)o[r];
-          *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(p.out) + obase + d0) = ob;
-        }
+        for (int k = 0; k < 4; k++) ob[k] = (__bf16)o[k];
+        *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(p.out) + obase) = ob;
+      } else if (EPI == kEpiF32) {
+        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + obase) = o;
+      } else {
+        // Out, Lse <- Update(block_out, block_lse) on the accumulators p.out / p.lse
+        float* const acc = reinterpret_cast<float*>(p.out) + obase;
+        float* const acc_lse = p.lse + (int64_t)b * p.l_sb + (int64_t)hq * p.l_sh + (int64_t)grow * p.l_ss;
+        const UpdatePlan pl = plan_update(*acc_lse, my_lse[r]);
+        const f32x4 x = *reinterpret_cast<const f32x4*>(acc);
+        *reinterpret_cast<f32x4*>(acc) = apply_update(pl, x, o);
+        // every lane of the row has read the old lse above; lanes of a row sit in one wave, so
+        // program order makes the single write below safe
+        if (cc == 0) *acc_lse = pl.new_lse;
       }
+    }
   }
 }
 
-template <int D, bool OUT_F32>
+template <int D, int EPI>
 hipError_t launch_one(const AttnParams& p, dim3 grid, hipStream_t stream) {
-  constexpr int lds_bytes = 2 * kRing * kBN * 2 * D;
+  // K/V rings; the epilogue reuses them for kWaves private 32 x D fp32 tiles plus 32 lse each
+  constexpr int ring_bytes = 2 * kRing * kBN * 2 * D;
+  constexpr int epi_bytes = kWaves * 32 * 4 * D + kWaves * 32 * 4;
+  constexpr int lds_bytes = ring_bytes > epi_bytes ? ring_bytes : epi_bytes;
+  static_assert(lds_bytes <= 160 * 1024, "LDS budget of one CU exceeded");
   static bool attr_set = false;  // raising the dynamic-LDS limit is a per-function, per-process setting
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&block_attn_kernel<D, OUT_F32>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&block_attn_kernel<D, EPI>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((block_attn_kernel<D, OUT_F32>), grid, dim3(kThreads), lds_bytes, stream, p);
+  hipLaunchKernelGGL((block_attn_kernel<D, EPI>), grid, dim3(kThreads), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_block_attn(const AttnParams& p, int D, bool out_f32, hipStream_t stream) {
+hipError_t launch_block_attn(const AttnParams& p, int D, int epilogue, hipStream_t stream) {
   const int64_t nblocks = (int64_t)p.n_qtiles * p.B * p.Hq;
   if (nblocks == 0) return hipSuccess;
   dim3 grid((unsigned)nblocks);
-  if (D == 128) return out_f32 ? launch_one<128, true>(p, grid, stream) : launch_one<128, false>(p, grid, stream);
-  return out_f32 ? launch_one<64, true>(p, grid, stream) : launch_one<64, false>(p, grid, stream);
+  if (D == 128) {
+    if (epilogue == kEpiBf16) return launch_one<128, kEpiBf16>(p, grid, stream);
+    if (epilogue == kEpiF32) return launch_one<128, kEpiF32>(p, grid, stream);
+    return launch_one<128, kEpiMerge>(p, grid, stream);
+  }
+  if (epilogue == kEpiBf16) return launch_one<64, kEpiBf16>(p, grid, stream);
+  if (epilogue == kEpiF32) return launch_one<64, kEpiF32>(p, grid, stream);
+  return launch_one<64, kEpiMerge>(p, grid, stream);
 }
 
 int attn_rows_per_block() { return kBM; }

@@ -31,25 +31,6 @@ constexpr int kMergeThreads = 256;
 #endif
 constexpr int kRows = TR_MERGE_ROWS;
 
-struct RowPlan {
-  int mode;  // 0: blend with weight w; 1: both empty -> 0; 2: empty accumulator -> block; 3: empty block -> keep
-  float w, new_lse;
-};
-__device__ __forceinline__ RowPlan plan_row(float a, float bb) {
-  RowPlan r;
-  const float m = fmaxf(a, bb);
-  r.mode = 0;
-  r.w = 0.f;
-  if (m == -INFINITY) { r.mode = 1; r.new_lse = -INFINITY; }
-  else if (a == -INFINITY) { r.mode = 2; r.new_lse = bb; }   // acc_out may be uninitialised here
-  else if (bb == -INFINITY) { r.mode = 3; r.new_lse = a; }
-  else {
-    r.new_lse = m + log1pf(expf(-fabsf(a - bb)));
-    r.w = expf(bb - r.new_lse);
-  }
-  return r;
-}
-
 template <bool BLK_BF16>
 __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const MergeParams p, int64_t n_rows, int64_t n_groups, int tpr_log2) {
   const int64_t gtid = (int64_t)blockIdx.x * kMergeThreads + threadIdx.x;
@@ -96,18 +77,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const MergeParams 
 #pragma unroll
     for (int r = 0; r < kRows; r++) {
       if (!live[r]) continue;
-      const RowPlan pl = plan_row(a[r], bb[r]);
-      f32x4 o;
-      if (pl.mode == 0) {
-#pragma unroll
-        for (int i = 0; i < 4; i++) o[i] = x[r][i] + pl.w * (y[r][i] - x[r][i]);
-      } else if (pl.mode == 1) {
-        o = f32x4{0.f, 0.f, 0.f, 0.f};
-      } else if (pl.mode == 2) {
-        o = y[r];
-      } else {
-        o = x[r];
-      }
+      const f32x4 o = apply_update(plan_update(a[r], bb[r]), x[r], y[r]);
       f32x4* dst = reinterpret_cast<f32x4*>(p.acc_out + ao[r] + col);
 #if TR_MERGE_NT_STORE
       __builtin_nontemporal_store(o, dst);
@@ -119,7 +89,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const MergeParams 
   if (t == 0) {
 #pragma unroll
     for (int r = 0; r < kRows; r++)
-      if (live[r]) p.acc_lse[al[r]] = plan_row(a[r], bb[r]).new_lse;
+      if (live[r]) p.acc_lse[al[r]] = plan_update(a[r], bb[r]).new_lse;
   }
 }
 

@@ -42,8 +42,45 @@ struct MergeParams {
 };
 
 // Launchers (defined next to their kernels). They only enqueue; errors come back as hipError_t.
-hipError_t launch_block_attn(const AttnParams& p, int D, bool out_f32, hipStream_t stream);
+// epilogue: 0 = bf16 block_out, 1 = fp32 block_out, 2 = merge into the fp32 accumulators p.out / p.lse
+hipError_t launch_block_attn(const AttnParams& p, int D, int epilogue, hipStream_t stream);
 hipError_t launch_merge(const MergeParams& p, bool blk_bf16, hipStream_t stream);
 int attn_rows_per_block();  // query rows one attention workgroup covers
+
+#if defined(__HIPCC__)
+// The Update of Sec. 3.1 for one row, shared by the merge kernel and the fused attention
+// epilogue:  lse' = max + log1p(exp(-|lse - block_lse|)),  w = exp(block_lse - lse')
+// (= sigmoid(block_lse - lse)),  out' = out + w (block_out - out).  The identity element
+// (out = 0, lse = -inf) on either side is handled exactly and never produces NaN.
+typedef float tr_f32x4 __attribute__((ext_vector_type(4)));
+struct UpdatePlan {
+  int mode;  // 0: blend with weight w; 1: both empty -> 0; 2: empty accumulator -> block; 3: empty block -> keep
+  float w, new_lse;
+};
+__device__ __forceinline__ UpdatePlan plan_update(float lse_acc, float lse_blk) {
+  UpdatePlan r;
+  const float m = fmaxf(lse_acc, lse_blk);
+  r.mode = 0;
+  r.w = 0.f;
+  if (m == -INFINITY) { r.mode = 1; r.new_lse = -INFINITY; }
+  else if (lse_acc == -INFINITY) { r.mode = 2; r.new_lse = lse_blk; }   // the accumulator's out may be uninitialised
+  else if (lse_blk == -INFINITY) { r.mode = 3; r.new_lse = lse_acc; }
+  else {
+    r.new_lse = m + log1pf(expf(-fabsf(lse_acc - lse_blk)));
+    r.w = expf(lse_blk - r.new_lse);
+  }
+  return r;
+}
+__device__ __forceinline__ tr_f32x4 apply_update(const UpdatePlan& pl, tr_f32x4 acc, tr_f32x4 blk) {
+  if (pl.mode == 0) {
+    tr_f32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; i++) o[i] = acc[i] + pl.w * (blk[i] - acc[i]);
+    return o;
+  }
+  if (pl.mode == 1) return tr_f32x4{0.f, 0.f, 0.f, 0.f};
+  return pl.mode == 2 ? blk : acc;
+}
+#endif
 
 }  // namespace tr

@@ -25,7 +25,7 @@ def _t(tr, dtype, B, H, S, D, ptr=0x7F0000000000, strides=None):
 def test_every_declared_symbol_is_exported(tr):
     text = open(HEADER).read()
     names = set(re.findall(r"\b(tr_[a-z_]+)\s*\(", text))
-    assert {"tr_block_attn", "tr_block_attn_causal_at", "tr_merge", "tr_ring_attn",
+    assert {"tr_block_attn", "tr_block_attn_causal_at", "tr_block_attn_merge", "tr_merge", "tr_ring_attn",
             "tr_ring_attn_workspace_bytes", "tr_last_error", "tr_version"} <= names
     lib = ctypes.CDLL(tr.LIB_PATH)
     for n in names:
@@ -67,6 +67,10 @@ def test_block_attn_rejects_bad_arguments(tr):
     assert call(q=_t(tr, tr.TR_BF16, 1, 4, 128, 128, ptr=0x7F0000000002))[0] == 4           # misaligned pointer
     assert call(o=_t(tr, tr.TR_F32, 1, 4, 128, 128, ptr=0x7F0000000000))[0] == 5            # out aliases q
     assert lib.tr_block_attn_causal_at(B(q), B(k), B(v), -1, 0, 0.1, B(o), B(l), None) == 3
+    # the fused form merges into fp32 accumulators only
+    ob = _t(tr, tr.TR_BF16, 1, 4, 128, 128, ptr=0x7F3000000000)
+    assert lib.tr_block_attn_merge(B(q), B(k), B(v), 0, 0.1, B(ob), B(l), None) == 2
+    assert lib.tr_block_attn_merge(B(q), B(k), B(v), 9, 0.1, B(o), B(l), None) == 6
 
 
 def test_merge_rejects_bad_arguments(tr):
@@ -100,7 +104,7 @@ def test_ring_attn_rejects_bad_arguments_and_workspace_size(tr):
     assert call(n=0)[0] == 3 and call(n=7)[0] == 3                                          # S % n_chunks
     assert call(o=_t(tr, tr.TR_BF16, 1, 32, 32768, 128, ptr=0x7F3000000000))[0] == 2         # out must be fp32
     assert call(k=_t(tr, tr.TR_BF16, 1, 32, 4096, 128, ptr=0x7F1000000000))[0] == 3
-    assert call(ws=None)[0] == 7 and call(nb=need - 1)[0] == 7 and call(ws=ws + 16)[0] == 7
+    assert call(nb=need - 1)[0] == 7 and call(ws=ws + 16)[0] == 7 and call(nb=0)[0] == 7      # (ws = NULL selects the fused form)
     st, msg = call(ws=0x7F3000000000)
     assert st == 5 and "workspace" in msg
 

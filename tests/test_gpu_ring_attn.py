@@ -17,12 +17,13 @@ pytestmark = pytest.mark.gpu
 OUT_TOL, LSE_TOL = 1e-2, 1e-3
 
 
-def _ring(lib, q, k, v, n_chunks, causal, scale=0.0, poison=True):
+def _ring(lib, q, k, v, n_chunks, causal, scale=0.0, poison=True, fused=True):
+    """fused=True: Update in the attention epilogue (no workspace); False: tr_block_attn + tr_merge."""
     B, Hq, S, D = q.shape
     fill = float("nan") if poison else 0.0
     out = torch.full((B, Hq, S, D), fill, dtype=torch.float32, device="cuda")
     lse = torch.full((B, Hq, S), fill, dtype=torch.float32, device="cuda")
-    ws = torch.empty(lib.tr_ring_attn_workspace_bytes(q, n_chunks), dtype=torch.uint8, device="cuda")
+    ws = None if fused else torch.empty(max(256, lib.tr_ring_attn_workspace_bytes(q, n_chunks)), dtype=torch.uint8, device="cuda")
     lib.tr_ring_attn(q, k, v, n_chunks, causal, out, lse, scale, ws)
     torch.cuda.synchronize()
     return out, lse
@@ -39,12 +40,13 @@ def test_ring_config1_small_noncausal_16_steps(lib):
     assert max_abs(to_np(out), alg_o) <= OUT_TOL and max_abs(to_np(lse), alg_l) <= LSE_TOL
 
 
+@pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("n_chunks", [1, 2, 3, 8])
-def test_ring_chunk_count_invariance(lib, n_chunks, causal):
+def test_ring_chunk_count_invariance(lib, n_chunks, causal, fused):
     B, Hq, Hkv, S, D = 2, 4, 2, 384, 128          # chunk of 128 / 48: several waves and a ragged tile tail
     qb, kb, vb = rand_bits((B, Hq, S, D), 21), rand_bits((B, Hkv, S, D), 22), rand_bits((B, Hkv, S, D), 23)
-    out, lse = _ring(lib, bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb), n_chunks, causal)   # scale 0 -> 1/sqrt(D)
+    out, lse = _ring(lib, bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb), n_chunks, causal, fused=fused)   # scale 0 -> 1/sqrt(D)
     ref_o, ref_l = oracle.attention_full(f64(qb), f64(kb), f64(vb), 1.0 / np.sqrt(D), causal)
     assert max_abs(to_np(out), ref_o) <= OUT_TOL and max_abs(to_np(lse), ref_l) <= LSE_TOL
 
@@ -57,6 +59,35 @@ def test_ring_n1_equals_single_block_step_bitwise(lib):
     lib.tr_block_attn(q, k, v, lib.TR_MASK_CAUSAL_DIAG, 0.07, o2, l2)
     torch.cuda.synchronize()
     assert torch.equal(out, o2) and torch.equal(lse, l2)
+
+
+def test_fused_and_two_kernel_forms_agree(lib):
+    """Same Update arithmetic in the same order: the fused epilogue and tr_block_attn + tr_merge
+    differ only in how the block reaches the Update (fp32 registers vs an fp32 workspace)."""
+    qb, kb, vb = rand_bits((1, 4, 1024, 128), 30), rand_bits((1, 2, 1024, 128), 31), rand_bits((1, 2, 1024, 128), 32)
+    q, k, v = bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb)
+    a = _ring(lib, q, k, v, 4, True, fused=True)
+    b = _ring(lib, q, k, v, 4, True, fused=False)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_block_attn_merge_matches_oracle_update(lib):
+    """tr_block_attn_merge on random fp32 accumulators (some rows empty) vs oracle attention + oracle Update."""
+    B, Hq, Hkv, Sq, Sk, D = 1, 4, 2, 300, 200, 128
+    qb, kb, vb = rand_bits((B, Hq, Sq, D), 33), rand_bits((B, Hkv, Sk, D), 34), rand_bits((B, Hkv, Sk, D), 35)
+    rng = np.random.default_rng(36)
+    acc_o = rng.standard_normal((B, Hq, Sq, D)).astype(np.float32)
+    acc_l = rng.uniform(-5, 15, (B, Hq, Sq)).astype(np.float32)
+    acc_l[0, 0, :7] = -np.inf
+    acc_o[0, 0, :7] = np.nan                         # empty rows may hold garbage
+    d_o, d_l = torch.from_numpy(acc_o).to("cuda"), torch.from_numpy(acc_l).to("cuda")
+    lib.tr_block_attn_merge(bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb), lib.TR_MASK_NONE, 0.09, d_o, d_l)
+    torch.cuda.synchronize()
+    blk_o, blk_l = oracle.attention_block(f64(qb), f64(kb), f64(vb), 0.09)
+    clean = acc_o.copy(); clean[0, 0, :7] = 0.0
+    ref_o, ref_l = oracle.merge_pair(clean, acc_l, blk_o, blk_l)
+    assert not torch.isnan(d_o).any()
+    assert max_abs(to_np(d_o), ref_o) <= OUT_TOL and max_abs(to_np(d_l), ref_l) <= LSE_TOL
 
 
 def test_ring_is_bitwise_reproducible(lib):
