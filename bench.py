@@ -80,6 +80,26 @@ def bench_block_step(tr, wl, steps, warmup):
     }
 
 
+def bench_step_fused(tr, wl, steps, warmup):
+    """The same block step as one kernel: tr_block_attn_merge (Update applied in the attention epilogue)."""
+    import torch
+    cfg = wl.CONFIGS["cfg2_block"]
+    qb, kb, vb = wl.make_qkv_bits(cfg)
+    q, k, v = _dev(qb), _dev(kb), _dev(vb)
+    acc_o = torch.zeros((cfg.B, cfg.Hq, cfg.S, cfg.D), dtype=torch.float32, device="cuda")
+    acc_l = torch.full((cfg.B, cfg.Hq, cfg.S), float("-inf"), dtype=torch.float32, device="cuda")
+    for _ in range(warmup):
+        tr.tr_block_attn_merge(q, k, v, tr.TR_MASK_NONE, cfg.scale, acc_o, acc_l)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in ev:
+        a.record(); tr.tr_block_attn_merge(q, k, v, tr.TR_MASK_NONE, cfg.scale, acc_o, acc_l); b.record()
+    torch.cuda.synchronize()
+    ms = sum(_event_ms(ev)) / steps
+    flops = 4.0 * cfg.S * cfg.S * cfg.D * cfg.Hq * cfg.B
+    return {"workload": "cfg2 block step as one kernel (tr_block_attn_merge)", "ms": ms,
+            "tflops": flops / (ms * 1e-3) / 1e12, "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+
+
 def bench_block_diag(tr, wl, steps, warmup):
     """The diagonal-causal variant of the block step (half the pairs)."""
     import torch
@@ -128,7 +148,8 @@ def bench_merge_only(tr, wl, steps, warmup):
             "bytes_per_merge": per_call_bytes, "gbs": gbs, "frac_hbm_peak": gbs / PEAK_HBM_GBS}
 
 
-def bench_ring(tr, wl, name, steps, warmup):
+def bench_ring(tr, wl, name, steps, warmup, fused):
+    """tr_ring_attn over a whole sequence; fused: Update in the attention epilogue (no workspace), else two kernels."""
     import torch
     cfg = wl.CONFIGS[name]
     g = torch.Generator(device="cuda").manual_seed(cfg.seed)
@@ -136,7 +157,7 @@ def bench_ring(tr, wl, name, steps, warmup):
     q, k, v = mk(cfg.Hq), mk(cfg.Hkv), mk(cfg.Hkv)
     out = torch.empty((cfg.B, cfg.Hq, cfg.S, cfg.D), dtype=torch.float32, device="cuda")
     lse = torch.empty((cfg.B, cfg.Hq, cfg.S), dtype=torch.float32, device="cuda")
-    ws = torch.empty(tr.tr_ring_attn_workspace_bytes(q, cfg.n_chunks), dtype=torch.uint8, device="cuda")
+    ws = None if fused else torch.empty(tr.tr_ring_attn_workspace_bytes(q, cfg.n_chunks), dtype=torch.uint8, device="cuda")
     for _ in range(warmup):
         tr.tr_ring_attn(q, k, v, cfg.n_chunks, cfg.causal, out, lse, cfg.scale, ws)
     torch.cuda.synchronize()
@@ -150,12 +171,13 @@ def bench_ring(tr, wl, name, steps, warmup):
     diag_steps = n if cfg.causal else 0
     flops = cfg.B * cfg.Hq * cfg.D * (4.0 * C * C * full_steps + 2.0 * C * (C + 1) * diag_steps)
     return {"workload": f"{name}: S={cfg.S} as {n} chunks, Hq={cfg.Hq}, Hkv={cfg.Hkv}, causal={cfg.causal}",
+            "form": "Update fused into the attention epilogue" if fused else "tr_block_attn + tr_merge per step",
             "block_steps": full_steps + diag_steps, "ms": ms, "tflops": flops / (ms * 1e-3) / 1e12,
             "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
 
 
-def cpu_baseline(wl, budget_s=20.0):
-    """The fp64 oracle on heads of the same block step, on this machine's host cores."""
+def cpu_baseline(wl, budget_s=12.0):
+    """The fp64 oracle on heads of the same block step, on this machine's host cores, for about budget_s seconds."""
     import oracle
     try:
         from threadpoolctl import threadpool_info
@@ -166,15 +188,16 @@ def cpu_baseline(wl, budget_s=20.0):
     qb, kb, vb = wl.make_qkv_bits(cfg)
     f = wl.bf16_bits_to_f64
     heads, t_used = 0, 0.0
-    while heads < cfg.Hq and (heads == 0 or t_used * (heads + 1) / heads < budget_s):
-        h = heads
+    while heads == 0 or t_used < budget_s:
+        h = heads % cfg.Hq
         t0 = time.perf_counter()
         oracle.attention_block(f(qb[:, h:h + 1]), f(kb[:, h:h + 1]), f(vb[:, h:h + 1]), cfg.scale)
         t_used += time.perf_counter() - t0
         heads += 1
     flops = 4.0 * cfg.S * cfg.S * cfg.D * heads
     return {"value": flops / t_used / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{heads} of {cfg.Hq} heads of the 4096x4096 D=128 block step, fp64 numpy, {t_used:.1f} s"}
+            "sample": f"{heads} head-passes (heads taken cyclically out of {cfg.Hq}) of the 4096x4096 D=128 block step, "
+                      f"fp64 numpy, {t_used:.1f} s"}
 
 
 def main():
@@ -231,10 +254,12 @@ def main():
     if not args.no_extras:
         ex_steps = max(3, min(args.steps, 10))
         line["extras"] = {
+            "step_fused": bench_step_fused(tr, wl, ex_steps, 2),
             "block_diag": bench_block_diag(tr, wl, ex_steps, 2),
             "merge_only": bench_merge_only(tr, wl, 3, 1),
-            "ring_cfg3": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1),
-            "ring_cfg5": bench_ring(tr, wl, "cfg5_gqa", 2, 1),
+            "ring_cfg3": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True),
+            "ring_cfg3_two_kernel": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=False),
+            "ring_cfg5": bench_ring(tr, wl, "cfg5_gqa", 2, 1, fused=True),
         }
         torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
