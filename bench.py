@@ -47,19 +47,23 @@ def bench_block_step(tr, wl, steps, warmup):
     acc_l = torch.full((B, H, S), float("-inf"), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
 
+    # Per-kernel durations: each launch carries its own start/stop HIP events in the dispatch
+    # (tr_time_next_kernel), on the stream the kernels run on, so the event pair brackets the
+    # kernel alone; the whole step is timed by the host clock around the K steps.
     def step(ev=None):
         if ev is not None:
-            ev[0].record(stream)
+            tr.tr_time_next_kernel(ev[0], ev[1])
         tr.tr_block_attn(q, k, v, tr.TR_MASK_NONE, cfg.scale, blk_o, blk_l, stream)
         if ev is not None:
-            ev[1].record(stream)
+            tr.tr_time_next_kernel(ev[2], ev[3])
         tr.tr_merge(acc_o, acc_l, blk_o, blk_l, stream)
-        if ev is not None:
-            ev[2].record(stream)
 
     for _ in range(warmup):
         step()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    for evs in events:          # make torch create the handles (a first record) outside the timed region
+        for e in evs:
+            e.record(stream)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
@@ -68,7 +72,7 @@ def bench_block_step(tr, wl, steps, warmup):
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / steps
     attn_ms = _event_ms([(e[0], e[1]) for e in events])
-    merge_ms = _event_ms([(e[1], e[2]) for e in events])
+    merge_ms = _event_ms([(e[2], e[3]) for e in events])
     attn_avg, merge_avg = sum(attn_ms) / steps, sum(merge_ms) / steps
     flops = 4.0 * S * S * D * H * B                              # algorithmic: 4*D per (q,k) pair
     merge_bytes = B * H * S * (D * (4 + 2 + 4) + 3 * 4)          # read acc fp32 + block bf16, write acc; 3 lse words

@@ -141,6 +141,16 @@ tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* 
 /* Bytes of workspace the two-kernel form of tr_ring_attn needs for these shapes (0 on invalid arguments). */
 size_t tr_ring_attn_workspace_bytes(const tr_tensor* q, int n_chunks);
 
+/*
+ * Measurement aid (no operation of the paper): arms two hipEvent_t handles (either may be
+ * NULL; both NULL disarms) for the calling thread.  The next kernel any entry point launches
+ * from this thread carries them in its dispatch: start_event then holds the time the kernel
+ * began executing and stop_event the time it finished, so hipEventElapsedTime(start, stop)
+ * is the kernel's own duration without queueing gaps.  Only that one launch is timed
+ * (tr_ring_attn: its first kernel); the events stay owned by the caller.  Always TR_OK.
+ */
+tr_status tr_time_next_kernel(void* start_event, void* stop_event);
+
 /* Description of the last error on the calling thread ("" if none). Static storage. */
 const char* tr_last_error(void);
 

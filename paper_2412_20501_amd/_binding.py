@@ -56,6 +56,8 @@ def _load():
     lib.tr_ring_attn.argtypes = [P, P, P, ctypes.c_int, ctypes.c_int, P, P, ctypes.c_float,
                                  ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.tr_ring_attn.restype = ctypes.c_int
+    lib.tr_time_next_kernel.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    lib.tr_time_next_kernel.restype = ctypes.c_int
     lib.tr_ring_attn_workspace_bytes.argtypes = [P, ctypes.c_int]
     lib.tr_ring_attn_workspace_bytes.restype = ctypes.c_size_t
     lib.tr_last_error.argtypes = []
@@ -129,6 +131,22 @@ def tr_block_attn_merge(q, k, v, mask_kind, scale, out_acc, lse_acc, stream=None
 def tr_merge(out_acc, lse_acc, block_out, block_lse, stream=None):
     """Out, Lse <- Update(block_out, block_lse), in place on out_acc / lse_acc."""
     _check(_lib.tr_merge(desc(out_acc), desc(lse_acc), desc(block_out), desc(block_lse), _stream(stream)))
+
+
+def tr_time_next_kernel(start_event, stop_event):
+    """Arms two timing events for this thread's next kernel launch (see tokenring.h).
+
+    Accepts raw hipEvent_t handles (int) or torch.cuda.Event objects created with
+    enable_timing=True; a torch event is recorded once first if it has no handle yet, so
+    that torch creates it and later allows elapsed_time() on it.
+    """
+    def handle(ev):
+        if ev is None or isinstance(ev, int):
+            return ev
+        if not ev.cuda_event:
+            ev.record()
+        return ev.cuda_event
+    _check(_lib.tr_time_next_kernel(handle(start_event), handle(stop_event)))
 
 
 def tr_ring_attn_workspace_bytes(q, n_chunks) -> int:

@@ -10,6 +10,7 @@
 namespace {
 
 thread_local char g_err[512] = "";
+thread_local tr::TimingEvents g_timing = {nullptr, nullptr};
 
 tr_status fail(tr_status st, const char* fmt, ...) {
   va_list ap;
@@ -117,9 +118,24 @@ size_t align_up(size_t x) { return (x + kWsAlign - 1) / kWsAlign * kWsAlign; }
 
 }  // namespace
 
+namespace tr {
+TimingEvents take_timing_events() {
+  const TimingEvents ev = g_timing;
+  g_timing = {nullptr, nullptr};
+  return ev;
+}
+}  // namespace tr
+
 extern "C" {
 
 const char* tr_last_error(void) { return g_err; }
+
+tr_status tr_time_next_kernel(void* start_event, void* stop_event) {
+  g_err[0] = 0;
+  g_timing.start = static_cast<hipEvent_t>(start_event);
+  g_timing.stop = static_cast<hipEvent_t>(stop_event);
+  return TR_OK;
+}
 const char* tr_version(void) { return "tokenring-gfx950 0.1"; }
 
 tr_status tr_block_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int mask_kind, float scale,

@@ -528,8 +528,7 @@ hipError_t launch_one(const AttnParams& p, dim3 grid, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((block_attn_kernel<D, EPI>), grid, dim3(kThreads), lds_bytes, stream, p);
-  return hipGetLastError();
+  return launch_kernel(block_attn_kernel<D, EPI>, grid, dim3(kThreads), lds_bytes, stream, p);
 }
 
 }  // namespace

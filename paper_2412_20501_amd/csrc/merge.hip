@@ -68,9 +68,8 @@ hipError_t launch_merge(const MergeParams& p, bool blk_bf16, hipStream_t stream)
   const int64_t n_threads = n_rows << tpr_log2;
   const int64_t nblocks = (n_threads + kMergeThreads - 1) / kMergeThreads;
   dim3 grid((unsigned)nblocks), block(kMergeThreads);
-  if (blk_bf16) hipLaunchKernelGGL((merge_kernel<true>), grid, block, 0, stream, p, n_rows, tpr_log2);
-  else hipLaunchKernelGGL((merge_kernel<false>), grid, block, 0, stream, p, n_rows, tpr_log2);
-  return hipGetLastError();
+  if (blk_bf16) return launch_kernel(merge_kernel<true>, grid, block, 0, stream, p, n_rows, tpr_log2);
+  return launch_kernel(merge_kernel<false>, grid, block, 0, stream, p, n_rows, tpr_log2);
 }
 
 }  // namespace tr

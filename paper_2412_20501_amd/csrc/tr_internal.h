@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of libtokenring (not part of the ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "tokenring.h"
@@ -46,6 +47,22 @@ struct MergeParams {
 hipError_t launch_block_attn(const AttnParams& p, int D, int epilogue, hipStream_t stream);
 hipError_t launch_merge(const MergeParams& p, bool blk_bf16, hipStream_t stream);
 int attn_rows_per_block();  // query rows one attention workgroup covers
+
+// Events armed by tr_time_next_kernel for the calling thread; the next launch consumes them.
+struct TimingEvents { hipEvent_t start, stop; };
+TimingEvents take_timing_events();
+
+#if defined(__HIPCC__)
+// Every kernel of the library is launched through here.  With armed events the dispatch itself
+// carries them, so they hold the kernel's own begin and end timestamps (no queue gaps).
+template <typename Kernel, typename... Args>
+inline hipError_t launch_kernel(Kernel kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, Args... args) {
+  const TimingEvents ev = take_timing_events();
+  if (ev.start != nullptr || ev.stop != nullptr) hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, ev.start, ev.stop, 0, args...);
+  else hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, args...);
+  return hipGetLastError();
+}
+#endif
 
 #if defined(__HIPCC__)
 // The Update of Sec. 3.1 for one row, shared by the merge kernel and the fused attention

@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(tr):
     text = open(HEADER).read()
     names = set(re.findall(r"\b(tr_[a-z_]+)\s*\(", text))
     assert {"tr_block_attn", "tr_block_attn_causal_at", "tr_block_attn_merge", "tr_merge", "tr_ring_attn",
-            "tr_ring_attn_workspace_bytes", "tr_last_error", "tr_version"} <= names
+            "tr_ring_attn_workspace_bytes", "tr_time_next_kernel", "tr_last_error", "tr_version"} <= names
     lib = ctypes.CDLL(tr.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in tokenring.h but not exported"
