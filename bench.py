@@ -84,6 +84,28 @@ def bench_block_step(tr, wl, steps, warmup):
     }
 
 
+def bench_mfma_ceiling(tr, wl):
+    """MFMA-only kernel on operands drawn like the workload's (N(0,1), bf16), every CU busy: what the matrix
+    cores sustain on this chip for such data, for comparison with the attention kernel's rate."""
+    import torch
+    cfg = wl.CONFIGS["cfg2_block"]
+    g = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    ops = torch.randn(8192, dtype=torch.float32, device="cuda", generator=g).to(torch.bfloat16)
+    sink = torch.zeros(16, dtype=torch.float32, device="cuda")
+    n_blocks = torch.cuda.get_device_properties(0).multi_processor_count
+    tr.tr_probe_mfma(ops, sink, 2000, n_blocks)
+    rates = []
+    for _ in range(3):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        tr.tr_time_next_kernel(a, b)
+        flop = tr.tr_probe_mfma(ops, sink, 20000, n_blocks)     # about 6 ms
+        torch.cuda.synchronize()
+        rates.append(flop / (a.elapsed_time(b) * 1e-3) / 1e12)
+    best = max(rates)
+    return {"workload": f"MFMA-only loop, {n_blocks} workgroups x 8 waves, rotating N(0,1) bf16 operands",
+            "tflops": best, "frac_mfma_peak": best / PEAK_BF16_TFLOPS}
+
+
 def bench_step_fused(tr, wl, steps, warmup):
     """The same block step as one kernel: tr_block_attn_merge (Update applied in the attention epilogue)."""
     import torch
@@ -258,6 +280,7 @@ def main():
     if not args.no_extras:
         ex_steps = max(3, min(args.steps, 10))
         line["extras"] = {
+            "mfma_only_ceiling": bench_mfma_ceiling(tr, wl),
             "step_fused": bench_step_fused(tr, wl, ex_steps, 2),
             "block_diag": bench_block_diag(tr, wl, ex_steps, 2),
             "merge_only": bench_merge_only(tr, wl, 3, 1),

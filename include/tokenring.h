@@ -151,6 +151,20 @@ size_t tr_ring_attn_workspace_bytes(const tr_tensor* q, int n_chunks);
  */
 tr_status tr_time_next_kernel(void* start_event, void* stop_event);
 
+/*
+ * Measurement aid (no operation of the paper): launches a kernel that only issues dense
+ * 32x32x16 bf16 MFMAs, 8 waves per workgroup, on `n_blocks` workgroups, each wave running
+ * 8 * iters MFMAs that rotate through 8 operand pairs read from `operands` (device, 16 KiB:
+ * 16 fragments of 64 lanes x 8 bf16, first the 8 A then the 8 B fragments, 16-byte aligned;
+ * the values are the caller's choice, e.g. the distribution of the real workload).  Timed
+ * with tr_time_next_kernel it gives the MFMA rate the chip sustains for that data, the
+ * practical ceiling next to which an MFMA-bound kernel can be read.  `sink` (device, >= 4
+ * bytes) is only there to keep the results live.  *flop_out (host, may be NULL) receives the
+ * flop count of the launch.  Enqueues on hip_stream and returns without synchronising.
+ */
+tr_status tr_probe_mfma(const void* operands, size_t operand_bytes, void* sink, int iters, int n_blocks,
+                        double* flop_out, void* hip_stream);
+
 /* Description of the last error on the calling thread ("" if none). Static storage. */
 const char* tr_last_error(void);
 

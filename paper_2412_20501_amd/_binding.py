@@ -58,6 +58,9 @@ def _load():
     lib.tr_ring_attn.restype = ctypes.c_int
     lib.tr_time_next_kernel.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
     lib.tr_time_next_kernel.restype = ctypes.c_int
+    lib.tr_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
+                                  ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    lib.tr_probe_mfma.restype = ctypes.c_int
     lib.tr_ring_attn_workspace_bytes.argtypes = [P, ctypes.c_int]
     lib.tr_ring_attn_workspace_bytes.restype = ctypes.c_size_t
     lib.tr_last_error.argtypes = []
@@ -147,6 +150,14 @@ def tr_time_next_kernel(start_event, stop_event):
             ev.record()
         return ev.cuda_event
     _check(_lib.tr_time_next_kernel(handle(start_event), handle(stop_event)))
+
+
+def tr_probe_mfma(operands, sink, iters, n_blocks, stream=None) -> float:
+    """MFMA-only measurement kernel on bf16 `operands` (>= 8192 elements); returns the launch's flop count."""
+    flop = ctypes.c_double(0.0)
+    _check(_lib.tr_probe_mfma(operands.data_ptr(), operands.numel() * operands.element_size(), sink.data_ptr(),
+                              int(iters), int(n_blocks), ctypes.byref(flop), _stream(stream)))
+    return flop.value
 
 
 def tr_ring_attn_workspace_bytes(q, n_chunks) -> int:

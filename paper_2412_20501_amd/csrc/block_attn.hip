@@ -36,6 +36,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -172,6 +173,13 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     if (p.causal) wave_kv_end = max(0, min(p.Sk, min(qw0 + 31, p.Sq - 1) + p.causal_off + 1));
   }
   const int jw = (wave_kv_end + SUB - 1) / SUB;  // sub-tiles this wave has visible keys in
+  // wave-uniform loop bounds, forced into scalar registers so that every per-step test is one compare
+  const int jw_even = __builtin_amdgcn_readfirstlane(jw);                          // last even step index allowed
+  const int jw_odd = __builtin_amdgcn_readfirstlane(min(jw, 2 * n_tiles - 1));     // last odd step index allowed
+  // a sub-tile starting at kstart needs masking iff kstart > kmask_from
+  int kmask_from_v = p.Sk - SUB;
+  if (p.causal) kmask_from_v = min(kmask_from_v, qw0 + p.causal_off - SUB + 1);
+  const int kmask_from = __builtin_amdgcn_readfirstlane(kmask_from_v);
 
   const __bf16* kg = p.k + (int64_t)b * p.k_sb + (int64_t)hk * p.k_sh;
   const __bf16* vg = p.v + (int64_t)b * p.v_sb + (int64_t)hk * p.v_sh;
@@ -206,19 +214,27 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + lds_off);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(off), "s"(base) : "memory");
   };
-  auto issue_k = [&](int tile, int slot) __attribute__((always_inline)) {
-    const int t = min(tile, last_tile);
-    const __bf16* base = uniform_ptr(kg + (int64_t)t * kBN * p.k_ss);
+  // Tiles are issued strictly in order, so the tile base is a running wave-uniform pointer that
+  // stops advancing at the last tile (later issues re-read it with the clamped offsets).
+  const __bf16* k_next = uniform_ptr(kg);
+  const __bf16* v_next = uniform_ptr(vg);
+  const int64_t k_tile_stride = (int64_t)kBN * p.k_ss, v_tile_stride = (int64_t)kBN * p.v_ss;
+  int k_left = last_tile, v_left = last_tile;  // tiles still ahead of the pointer
+  auto issue_k = [&](int slot) __attribute__((always_inline)) {
+    const bool last = k_left <= 0;
 #pragma unroll
     for (int i = 0; i < IPW; i++)
-      dma16(base, t == last_tile ? k_off_last[i] : k_off[i], slot * TILE_BYTES + (wave * IPW + i) * 1024);
+      dma16(k_next, last ? k_off_last[i] : k_off[i], slot * TILE_BYTES + (wave * IPW + i) * 1024);
+    k_next = uniform_ptr(k_next + (last ? 0 : k_tile_stride));
+    k_left--;
   };
-  auto issue_v = [&](int tile, int slot) __attribute__((always_inline)) {
-    const int t = min(tile, last_tile);
-    const __bf16* base = uniform_ptr(vg + (int64_t)t * kBN * p.v_ss);
+  auto issue_v = [&](int slot) __attribute__((always_inline)) {
+    const bool last = v_left <= 0;
 #pragma unroll
     for (int i = 0; i < IPW; i++)
-      dma16(base, t == last_tile ? v_off_last[i] : v_off[i], (NS + slot) * TILE_BYTES + (wave * IPW + i) * 1024);
+      dma16(v_next, last ? v_off_last[i] : v_off[i], (NS + slot) * TILE_BYTES + (wave * IPW + i) * 1024);
+    v_next = uniform_ptr(v_next + (last ? 0 : v_tile_stride));
+    v_left--;
   };
 
   // Per-lane LDS read offsets.
@@ -246,6 +262,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
 #pragma unroll
     for (int i = 0; i < 16; i++) o_acc[db][i] = 0.f;
   float m_ref = -INFINITY;  // exponent reference of this query, in raw (unscaled) score units
+  float mc = 0.f;           // m_ref * c2 (0 while m_ref is -inf), kept alongside m_ref
   float l_run = 0.f;        // this lane's share of the running sum of exp
   const float c2 = p.scale * 1.4426950408889634f;  // scale * log2(e)
 
@@ -297,8 +314,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     static_assert(16 % n_mfma == 0, "softmax elements must divide evenly over the MFMAs");
     constexpr unsigned v_imm = decltype(v_imm_c)::value, k_imm_next = decltype(k_imm_next_c)::value;
 
-    const bool need_mask = (kstart + SUB > p.Sk) || (p.causal && (kstart + SUB - 1 > qw0 + p.causal_off));
-    if (need_mask) {
+    if (kstart > kmask_from) {  // some key of the sub-tile is past Sk or above this wave's first diagonal
       int limit = p.Sk - 1;
       if (p.causal) limit = min(limit, qrow + p.causal_off);
 #pragma unroll
@@ -308,24 +324,35 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
       }
     }
 
-    const float mc = (m_ref == -INFINITY) ? 0.f : m_ref * c2;
     f32x16 acc;
 #pragma unroll
     for (int i = 0; i < 16; i++) acc[i] = 0.f;
     bf16x8 pv_ops[NPV], nxt[NQK];
     float tq[16], ex[16];
+    unsigned pw[8];
     float ps0 = 0.f, ps1 = 0.f;
-    // softmax element e passes stage A (fma) in slice e/EPM, stage B (exp2) one slice later and
-    // stage C (sum, convert) two slices later; the last two slices' leftovers drain after the loop
-    auto stage_a = [&](int e) __attribute__((always_inline)) { tq[e] = __builtin_fmaf(s_in[e], c2, -mc); };
-    auto stage_b = [&](int e) __attribute__((always_inline)) { ex[e] = __builtin_amdgcn_exp2f(tq[e]); };
-    auto stage_c = [&](int e) __attribute__((always_inline)) {
-      if (e & 1) {
-        ps1 += ex[e];
-        p_out[e >> 3][(e & 7) - 1] = (__bf16)ex[e - 1];
-        p_out[e >> 3][e & 7] = (__bf16)ex[e];
-      } else {
-        ps0 += ex[e];
+    // Softmax element group g (EPM elements) passes stage A (fma) in slice g-2, stage B (exp2) in
+    // slice g-1 and stage C (sum, convert) in slice g, so the stream ends with the last MFMA
+    // and nothing but the sum check is left behind it.  The convert is opaque to the compiler,
+    // which would otherwise sink all of them behind the slow-path branch.
+    auto stage_a = [&](int g) __attribute__((always_inline)) {
+#pragma unroll
+      for (int k = 0; k < EPM; k++) tq[g * EPM + k] = __builtin_fmaf(s_in[g * EPM + k], c2, -mc);
+    };
+    auto stage_b = [&](int g) __attribute__((always_inline)) {
+#pragma unroll
+      for (int k = 0; k < EPM; k++) ex[g * EPM + k] = __builtin_amdgcn_exp2f(tq[g * EPM + k]);
+    };
+    auto stage_c = [&](int g) __attribute__((always_inline)) {
+#pragma unroll
+      for (int k = 0; k < EPM; k++) {
+        const int e = g * EPM + k;
+        if (e & 1) {
+          ps1 += ex[e];
+          asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pw[e >> 1]) : "v"(ex[e - 1]), "v"(ex[e]));
+        } else {
+          ps0 += ex[e];
+        }
       }
     };
     __builtin_amdgcn_sched_barrier(0);
@@ -340,21 +367,19 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
         nxt[j] = load_k(j, k_imm_next);
         o_acc[j % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pv_ops[j], p_in[j / DB], o_acc[j % DB], 0, 0, 0);
       }
-#pragma unroll
-      for (int k = 0; k < EPM; k++) {
-        stage_a(i * EPM + k);
-        if (i >= 1) stage_b((i - 1) * EPM + k);
-        if (i >= 2) stage_c((i - 2) * EPM + k);
+      if (i == 0) {
+        __builtin_amdgcn_sched_barrier(0);  // the first MFMA issues before any softmax work
+        stage_a(0);
+        stage_b(0);
+        stage_a(1);
       }
+      if (i + 1 < n_mfma) stage_b(i + 1);
+      if (i + 2 < n_mfma) stage_a(i + 2);
+      stage_c(i);
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
-    for (int k = 0; k < EPM; k++) {
-      stage_b((n_mfma - 1) * EPM + k);
-      stage_c((n_mfma - 2) * EPM + k);
-    }
-#pragma unroll
-    for (int k = 0; k < EPM; k++) stage_c((n_mfma - 1) * EPM + k);
+    for (int h = 0; h < 2; h++) p_out[h] = __builtin_bit_cast(bf16x8, u32x4{pw[4 * h], pw[4 * h + 1], pw[4 * h + 2], pw[4 * h + 3]});
     float psum = ps0 + ps1;
 
     if (__any(!(psum <= kSumCap) || m_ref == -INFINITY)) {
@@ -371,7 +396,8 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
 #pragma unroll
         for (int i = 0; i < 16; i++) o_acc[db][i] *= a;
       m_ref = m_new;
-      const float mc2 = (m_ref == -INFINITY) ? 0.f : m_ref * c2;
+      mc = (m_ref == -INFINITY) ? 0.f : m_ref * c2;
+      const float mc2 = mc;
       float q0s = 0.f, q1s = 0.f;
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
@@ -392,11 +418,11 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
 
   // ---- prologue: K_0..K_2, V_0, V_1 into the rings
   if (n_tiles > 0) {
-    issue_k(0, 0);
-    issue_v(0, 0);
-    issue_k(1, 1);
-    issue_v(1, 1);
-    issue_k(2, 2);
+    issue_k(0);
+    issue_v(0);
+    issue_k(1);
+    issue_v(1);
+    issue_k(2);
   }
 #pragma unroll
   for (int ks = 0; ks < KS; ks++) asm volatile("" ::"v"(qf[ks]));  // Q is in registers before the loop
@@ -415,8 +441,8 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   bf16x8 pA[2], pB[2];
   constexpr unsigned kKt1 = SUB * RB;  // byte offset of the second sub-tile inside a tile
   if (n_tiles > 0) {
-    issue_k(3, 3 % NS);
-    issue_v(2, 2 % NS);
+    issue_k(3 % NS);
+    issue_v(2 % NS);
     if (jw > 0) {
       // S_0 = K_0[0:32] Q^T, plain (nothing to overlap with yet); operands of step 0 (K_0, kt 1)
 #pragma unroll
@@ -437,14 +463,14 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     constexpr int su = decltype(slot_c)::value, sp = (su + NS - 1) % NS, sn = (su + 1) % NS;
     __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * IPW));  // vmcnt only
     wg_barrier();                                    // B_u
-    issue_k(u + 3, (su + 3) % NS);
-    issue_v(u + 2, (su + 2) % NS);
+    issue_k((su + 3) % NS);   // K_{u+3}
+    issue_v((su + 2) % NS);   // V_{u+2}
     // step 2u: S of sub-tile 2u+1 (K_u, kt 1, already in `pre`); PV of sub-tile 2u-1 (V_{u-1}, kt 1);
     //          softmax of sub-tile 2u; prefetch (K_{u+1}, kt 0)
-    if (2 * u <= jw) step(2 * u * SUB, IC<0>{}, IC<sp * TILE_BYTES + kKt1>{}, IC<sn * TILE_BYTES>{}, sA, sB, pB, pA);
+    if (2 * u <= jw_even) step(2 * u * SUB, IC<0>{}, IC<sp * TILE_BYTES + kKt1>{}, IC<sn * TILE_BYTES>{}, sA, sB, pB, pA);
     // step 2u+1: S of sub-tile 2u+2 (K_{u+1}, kt 0); PV of sub-tile 2u (V_u, kt 0);
     //          softmax of sub-tile 2u+1; prefetch (K_{u+1}, kt 1)
-    if (u < n_tiles && 2 * u + 1 <= jw)
+    if (2 * u + 1 <= jw_odd)
       step((2 * u + 1) * SUB, IC<0>{}, IC<su * TILE_BYTES>{}, IC<sn * TILE_BYTES + kKt1>{}, sB, sA, pA, pB);
   };
   for (int u0 = 0; u0 <= n_tiles; u0 += NS) {

@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(tr):
     text = open(HEADER).read()
     names = set(re.findall(r"\b(tr_[a-z_]+)\s*\(", text))
     assert {"tr_block_attn", "tr_block_attn_causal_at", "tr_block_attn_merge", "tr_merge", "tr_ring_attn",
-            "tr_ring_attn_workspace_bytes", "tr_time_next_kernel", "tr_last_error", "tr_version"} <= names
+            "tr_ring_attn_workspace_bytes", "tr_time_next_kernel", "tr_probe_mfma", "tr_last_error", "tr_version"} <= names
     lib = ctypes.CDLL(tr.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in tokenring.h but not exported"
@@ -107,6 +107,17 @@ def test_ring_attn_rejects_bad_arguments_and_workspace_size(tr):
     assert call(nb=need - 1)[0] == 7 and call(ws=ws + 16)[0] == 7 and call(nb=0)[0] == 7      # (ws = NULL selects the fused form)
     st, msg = call(ws=0x7F3000000000)
     assert st == 5 and "workspace" in msg
+
+
+def test_probe_rejects_bad_arguments(tr):
+    lib = tr.raw_lib()
+    ok_ptr, sink = 0x7F0000000000, 0x7F0000100000
+    assert lib.tr_probe_mfma(None, 16384, sink, 10, 4, None, None) == 1
+    assert lib.tr_probe_mfma(ok_ptr, 16383, sink, 10, 4, None, None) == 3
+    assert lib.tr_probe_mfma(ok_ptr + 2, 16384, sink, 10, 4, None, None) == 4
+    assert lib.tr_probe_mfma(ok_ptr, 16384, sink, 0, 4, None, None) == 3
+    assert lib.tr_probe_mfma(ok_ptr, 16384, sink, 10, 0, None, None) == 3
+    assert b"tr_probe_mfma" in lib.tr_last_error()
 
 
 def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
