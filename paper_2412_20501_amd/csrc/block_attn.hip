@@ -511,30 +511,51 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   if (EPI != kEpiMerge && hf == 0 && qrow < p.Sq)
     p.lse[(int64_t)b * p.l_sb + (int64_t)hq * p.l_sh + (int64_t)qrow * p.l_ss] = lse_blk;
   const int rr = lane / CPRF, cc = lane % CPRF;
+  constexpr int NIT = 32 / RPI_OUT;
+  const int64_t o_bh = (int64_t)b * p.o_sb + (int64_t)hq * p.o_sh + 4 * cc;
+  const int64_t l_bh = (int64_t)b * p.l_sb + (int64_t)hq * p.l_sh;
+  if (EPI == kEpiMerge) {
+    // Out, Lse <- Update(block_out, block_lse) on the accumulators p.out / p.lse.  All of the
+    // wave's accumulator rows are fetched first (the O registers are free by now), so their
+    // latencies overlap instead of each load waiting behind the previous row's store.  Rows
+    // past Sq fetch the last valid row and are never stored.
+    float* const acc_out = reinterpret_cast<float*>(p.out);
+    f32x4 x[NIT];
+    float la[NIT];
 #pragma unroll
-  for (int it = 0; it < 32 / RPI_OUT; it++) {
-    const int r = it * RPI_OUT + rr;
-    const int grow = qw0 + r;
-    const f32x4 o = *reinterpret_cast<const f32x4*>(my + r * ROWB + ((cc ^ (r & 15)) << 4));
-    if (grow < p.Sq) {
-      const int64_t obase = (int64_t)b * p.o_sb + (int64_t)hq * p.o_sh + (int64_t)grow * p.o_ss + 4 * cc;
-      if (EPI == kEpiBf16) {
-        bf16x4 ob;
+    for (int it = 0; it < NIT; it++) {
+      const int grow = min(qw0 + it * RPI_OUT + rr, p.Sq - 1);
+      x[it] = *reinterpret_cast<const f32x4*>(acc_out + o_bh + (int64_t)grow * p.o_ss);
+      la[it] = p.lse[l_bh + (int64_t)grow * p.l_ss];
+    }
 #pragma unroll
-        for (int k = 0; k < 4; k++) ob[k] = (__bf16)o[k];
-        *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(p.out) + obase) = ob;
-      } else if (EPI == kEpiF32) {
-        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + obase) = o;
-      } else {
-        // Out, Lse <- Update(block_out, block_lse) on the accumulators p.out / p.lse
-        float* const acc = reinterpret_cast<float*>(p.out) + obase;
-        float* const acc_lse = p.lse + (int64_t)b * p.l_sb + (int64_t)hq * p.l_sh + (int64_t)grow * p.l_ss;
-        const UpdatePlan pl = plan_update(*acc_lse, my_lse[r]);
-        const f32x4 x = *reinterpret_cast<const f32x4*>(acc);
-        *reinterpret_cast<f32x4*>(acc) = apply_update(pl, x, o);
-        // every lane of the row has read the old lse above; lanes of a row sit in one wave, so
-        // program order makes the single write below safe
-        if (cc == 0) *acc_lse = pl.new_lse;
+    for (int it = 0; it < NIT; it++) {
+      const int r = it * RPI_OUT + rr;
+      const int grow = qw0 + r;
+      const f32x4 o = *reinterpret_cast<const f32x4*>(my + r * ROWB + ((cc ^ (r & 15)) << 4));
+      const UpdatePlan pl = plan_update(la[it], my_lse[r]);
+      if (grow < p.Sq) {
+        *reinterpret_cast<f32x4*>(acc_out + o_bh + (int64_t)grow * p.o_ss) = apply_update(pl, x[it], o);
+        // every lane of the row took the old lse in the first loop, so the single write is safe
+        if (cc == 0) p.lse[l_bh + (int64_t)grow * p.l_ss] = pl.new_lse;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int it = 0; it < NIT; it++) {
+      const int r = it * RPI_OUT + rr;
+      const int grow = qw0 + r;
+      const f32x4 o = *reinterpret_cast<const f32x4*>(my + r * ROWB + ((cc ^ (r & 15)) << 4));
+      if (grow < p.Sq) {
+        const int64_t oidx = o_bh + (int64_t)grow * p.o_ss;
+        if (EPI == kEpiBf16) {
+          bf16x4 ob;
+#pragma unroll
+          for (int k = 0; k < 4; k++) ob[k] = (__bf16)o[k];
+          *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(p.out) + oidx) = ob;
+        } else {
+          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + oidx) = o;
+        }
       }
     }
   }
