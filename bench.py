@@ -174,8 +174,9 @@ def bench_merge_only(tr, wl, steps, warmup):
             "bytes_per_merge": per_call_bytes, "gbs": gbs, "frac_hbm_peak": gbs / PEAK_HBM_GBS}
 
 
-def bench_ring(tr, wl, name, steps, warmup, fused):
-    """tr_ring_attn over a whole sequence; fused: Update in the attention epilogue (no workspace), else two kernels."""
+def bench_ring(tr, wl, name, steps, warmup, fused, schedule=None, n_inner=1):
+    """tr_ring_attn over a whole sequence; fused: Update in the attention epilogue (no workspace), else two kernels.
+    schedule: None = tr_ring_attn (Algorithm 1), else a TR_SCHED_* value run through tr_ring_attn_sched."""
     import torch
     cfg = wl.CONFIGS[name]
     g = torch.Generator(device="cuda").manual_seed(cfg.seed)
@@ -184,19 +185,30 @@ def bench_ring(tr, wl, name, steps, warmup, fused):
     out = torch.empty((cfg.B, cfg.Hq, cfg.S, cfg.D), dtype=torch.float32, device="cuda")
     lse = torch.empty((cfg.B, cfg.Hq, cfg.S), dtype=torch.float32, device="cuda")
     ws = None if fused else torch.empty(tr.tr_ring_attn_workspace_bytes(q, cfg.n_chunks), dtype=torch.uint8, device="cuda")
+
+    def run():
+        if schedule is None:
+            tr.tr_ring_attn(q, k, v, cfg.n_chunks, cfg.causal, out, lse, cfg.scale, ws)
+        else:
+            tr.tr_ring_attn_sched(q, k, v, cfg.n_chunks, cfg.causal, schedule, out, lse, cfg.scale, n_inner)
+
     for _ in range(warmup):
-        tr.tr_ring_attn(q, k, v, cfg.n_chunks, cfg.causal, out, lse, cfg.scale, ws)
+        run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        tr.tr_ring_attn(q, k, v, cfg.n_chunks, cfg.causal, out, lse, cfg.scale, ws)
+        run()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
     n, C = cfg.n_chunks, cfg.chunk
+    if schedule == tr.TR_SCHED_ZIGZAG:      # 2n segments of half the length
+        n, C = 2 * n, C // 2
     full_steps = n * (n - 1) // 2 if cfg.causal else n * n
     diag_steps = n if cfg.causal else 0
     flops = cfg.B * cfg.Hq * cfg.D * (4.0 * C * C * full_steps + 2.0 * C * (C + 1) * diag_steps)
-    return {"workload": f"{name}: S={cfg.S} as {n} chunks, Hq={cfg.Hq}, Hkv={cfg.Hkv}, causal={cfg.causal}",
+    sched_name = {None: "Algorithm 1", 0: "Algorithm 1", 1: "Ring Attention order", 2: "zigzag partition",
+                  3: f"hybrid, {n_inner} devices per node"}[schedule]
+    return {"workload": f"{name}: S={cfg.S} as {n} segments, Hq={cfg.Hq}, Hkv={cfg.Hkv}, causal={cfg.causal}, {sched_name}",
             "form": "Update fused into the attention epilogue" if fused else "tr_block_attn + tr_merge per step",
             "block_steps": full_steps + diag_steps, "ms": ms, "tflops": flops / (ms * 1e-3) / 1e12,
             "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
@@ -286,6 +298,8 @@ def main():
             "merge_only": bench_merge_only(tr, wl, 3, 1),
             "ring_cfg3": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True),
             "ring_cfg3_two_kernel": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=False),
+            "ring_cfg3_zigzag": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True, schedule=tr.TR_SCHED_ZIGZAG),
+            "ring_cfg3_hybrid_2x4": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True, schedule=tr.TR_SCHED_HYBRID, n_inner=4),
             "ring_cfg5": bench_ring(tr, wl, "cfg5_gqa", 2, 1, fused=True),
         }
         torch.cuda.empty_cache()

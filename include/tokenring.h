@@ -138,6 +138,35 @@ tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* 
                        const tr_tensor* out, const tr_tensor* lse, float scale,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Order in which tr_ring_attn_sched runs the block steps (all "devices" replayed on one GPU). */
+typedef enum {
+  TR_SCHED_TOKENRING = 0,      /* Algorithm 1: Q circulates, device j keeps K_j, V_j              */
+  TR_SCHED_RING_ATTENTION = 1, /* Sec. 2.1: K/V circulate, device j keeps Q_j                     */
+  TR_SCHED_ZIGZAG = 2,         /* Sec. 3.3.2: 2n segments, device g owns g and 2n-1-g (causal)    */
+  TR_SCHED_HYBRID = 3          /* Sec. 3.3.3: Ring Attention between nodes, Algorithm 1 inside    */
+} tr_schedule;
+
+/*
+ * tr_ring_attn with a selectable schedule; the Update always runs in the attention epilogue
+ * (no workspace).  The sequence is cut into n_devices equal chunks (2 * n_devices segments for
+ * TR_SCHED_ZIGZAG, which requires causal != 0); S must be a multiple of that.
+ *   TR_SCHED_TOKENRING      for i, for j: Q chunk (j-i) mod n  x  K/V chunk j       (bitwise equal to
+ *                           tr_ring_attn with workspace == NULL)
+ *   TR_SCHED_RING_ATTENTION for i, for j: Q chunk j  x  K/V chunk (j-i) mod n
+ *   TR_SCHED_ZIGZAG         for i, for j: the Query pair {c, 2n-1-c}, c = (j-i) mod n, against the K/V pair
+ *                           {j, 2n-1-j}; of the four segment pairs the causal rule keeps two full ones
+ *                           (three on i == 0, two of them diagonal), so every (i, j) carries the same work
+ *   TR_SCHED_HYBRID         n_devices = nodes x n_inner; for t < nodes, for i < n_inner, for node, for p:
+ *                           Q chunk node*n_inner + (p-i) mod n_inner  x  K/V chunk ((node-t) mod nodes)*n_inner + p
+ *                           (n_inner is ignored by the other schedules)
+ * With causal != 0 a step whose K/V segment lies after its Query segment is dropped and equal
+ * segments use the diagonal mask.  Every schedule reaches the same result up to fp32 rounding of
+ * the merge order; each is bitwise reproducible.  Tensors, scale and stream as in tr_ring_attn.
+ */
+tr_status tr_ring_attn_sched(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v,
+                             int n_devices, int causal, int schedule, int n_inner,
+                             const tr_tensor* out, const tr_tensor* lse, float scale, void* hip_stream);
+
 /* Bytes of workspace the two-kernel form of tr_ring_attn needs for these shapes (0 on invalid arguments). */
 size_t tr_ring_attn_workspace_bytes(const tr_tensor* q, int n_chunks);
 

@@ -7,11 +7,15 @@ from .tokenring_oracle import (  # noqa: F401
     attention_block,
     attention_full,
     attention_rows,
+    hybrid_order,
     merge_nary,
     merge_pair,
     merge_pair_sigmoid_form,
     ring_attention,
+    ring_attention_order,
     ring_schedule,
     softmax_weights,
+    zigzag_order,
     zigzag_segments,
+    zigzag_steps,
 )

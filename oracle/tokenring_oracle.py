@@ -228,3 +228,56 @@ def zigzag_segments(n_devices):
     """Zigzag partition of Sec. 3.3.2: the sequence is cut into 2N segments and device g
     holds segments g and 2N-1-g (four devices, eight segments: device 0 holds 0 and 7)."""
     return [(g, 2 * n_devices - 1 - g) for g in range(n_devices)]
+
+
+def ring_attention_order(n_chunks, causal):
+    """Ring Attention (Sec. 2.1) as (q_chunk, kv_chunk) pairs in execution order: device j keeps
+    Q_j and, at iteration i, holds the K/V chunk that started on device (j - i) mod N."""
+    pairs = []
+    for i in range(n_chunks):
+        for j in range(n_chunks):
+            kv = (j - i) % n_chunks
+            if causal and kv > j:
+                continue
+            pairs.append((j, kv))
+    return pairs
+
+
+def zigzag_steps(n_devices):
+    """TokenRing on the zigzag partition (Sec. 3.3.2), causal: (i, j, q_segment, kv_segment) in
+    execution order over 2N segments.  Device j keeps the K/V of its two segments; at iteration
+    i it holds the Query pair of device c = (j - i) mod N.  A pair of segments is computed iff
+    the K/V segment does not lie after the Query segment."""
+    owned = zigzag_segments(n_devices)
+    steps = []
+    for i in range(n_devices):
+        for j in range(n_devices):
+            c = (j - i) % n_devices
+            for qs in owned[c]:
+                for ks in owned[j]:
+                    if ks <= qs:
+                        steps.append((i, j, qs, ks))
+    return steps
+
+
+def zigzag_order(n_devices):
+    """zigzag_steps as plain (q_segment, kv_segment) pairs, the form ring_attention's ``order`` takes."""
+    return [(qs, ks) for (_, _, qs, ks) in zigzag_steps(n_devices)]
+
+
+def hybrid_order(n_nodes, per_node, causal):
+    """Multi-node scheme of Sec. 3.3.3 as (q_chunk, kv_chunk) pairs: K/V move between nodes as
+    in Ring Attention (after outer step t, device p of node m holds the K/V that started on
+    device p of node (m - t) mod M); inside every node Algorithm 1 circulates the node's own
+    Query chunks among its ``per_node`` devices."""
+    pairs = []
+    for t in range(n_nodes):
+        for i in range(per_node):
+            for m in range(n_nodes):
+                for p in range(per_node):
+                    qc = m * per_node + (p - i) % per_node
+                    kv = ((m - t) % n_nodes) * per_node + p
+                    if causal and kv > qc:
+                        continue
+                    pairs.append((qc, kv))
+    return pairs

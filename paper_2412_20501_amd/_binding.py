@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libtokenring.so")
 
 TR_BF16, TR_F32 = 0, 1
 TR_MASK_NONE, TR_MASK_CAUSAL_DIAG = 0, 1
+TR_SCHED_TOKENRING, TR_SCHED_RING_ATTENTION, TR_SCHED_ZIGZAG, TR_SCHED_HYBRID = 0, 1, 2, 3
 
 STATUS_NAMES = {
     0: "TR_OK", 1: "TR_ERR_NULL", 2: "TR_ERR_DTYPE", 3: "TR_ERR_SHAPE", 4: "TR_ERR_STRIDE",
@@ -61,6 +62,9 @@ def _load():
     lib.tr_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
                                   ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
     lib.tr_probe_mfma.restype = ctypes.c_int
+    lib.tr_ring_attn_sched.argtypes = [P, P, P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P, ctypes.c_float,
+                                       ctypes.c_void_p]
+    lib.tr_ring_attn_sched.restype = ctypes.c_int
     lib.tr_ring_attn_workspace_bytes.argtypes = [P, ctypes.c_int]
     lib.tr_ring_attn_workspace_bytes.restype = ctypes.c_size_t
     lib.tr_last_error.argtypes = []
@@ -158,6 +162,12 @@ def tr_probe_mfma(operands, sink, iters, n_blocks, stream=None) -> float:
     _check(_lib.tr_probe_mfma(operands.data_ptr(), operands.numel() * operands.element_size(), sink.data_ptr(),
                               int(iters), int(n_blocks), ctypes.byref(flop), _stream(stream)))
     return flop.value
+
+
+def tr_ring_attn_sched(q, k, v, n_devices, causal, schedule, out, lse, scale=0.0, n_inner=1, stream=None):
+    """tr_ring_attn with a selectable step order (TR_SCHED_*); Update fused into the attention epilogue."""
+    _check(_lib.tr_ring_attn_sched(desc(q), desc(k), desc(v), int(n_devices), int(bool(causal)), int(schedule), int(n_inner),
+                                   desc(out), desc(lse), float(scale), _stream(stream)))
 
 
 def tr_ring_attn_workspace_bytes(q, n_chunks) -> int:

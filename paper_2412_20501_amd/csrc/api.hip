@@ -5,6 +5,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <vector>
+
 #include "tr_internal.h"
 
 namespace {
@@ -111,6 +113,56 @@ tr_tensor chunk_view(const tr_tensor* t, int64_t c, int64_t C) {
   r.ptr = (char*)t->ptr + c * C * t->stride_s * elem_bytes(t->dtype);
   r.S = C;
   return r;
+}
+
+// One block step of a schedule: Query segment qs attends K/V segment ks (equal segments of S).
+struct RingStep { int qs, ks; };
+
+inline int pmod(int a, int n) { return ((a % n) + n) % n; }
+
+// Execution order of the block steps, all "devices" replayed in turn, and the number of equal
+// segments the sequence is cut into.  Under the causal rule a step whose K/V segment lies
+// after its Query segment is dropped (the caller masks ks == qs diagonally).
+//   TokenRing (Algorithm 1): iteration i, device j (holds K_j, V_j) works on Query chunk (j-i) mod n.
+//   Ring Attention (Sec. 2.1): device j keeps Q_j; at iteration i it holds K/V chunk (j-i) mod n.
+//   Zigzag (Sec. 3.3.2): 2n segments, device g owns segments g and 2n-1-g of Q, K and V; the
+//     Query pair circulates as in Algorithm 1.
+//   Hybrid (Sec. 3.3.3): n = nodes * n_inner devices; K/V travel between nodes as in Ring
+//     Attention (outer step t), Algorithm 1 runs among the n_inner devices of each node.
+int build_schedule(int schedule, int n, int n_inner, bool causal, std::vector<RingStep>& steps) {
+  steps.clear();
+  auto add = [&](int qs, int ks) {
+    if (!causal || ks <= qs) steps.push_back({qs, ks});
+  };
+  switch (schedule) {
+    case TR_SCHED_TOKENRING:
+      for (int i = 0; i < n; i++)
+        for (int j = 0; j < n; j++) add(pmod(j - i, n), j);
+      return n;
+    case TR_SCHED_RING_ATTENTION:
+      for (int i = 0; i < n; i++)
+        for (int j = 0; j < n; j++) add(j, pmod(j - i, n));
+      return n;
+    case TR_SCHED_ZIGZAG:
+      for (int i = 0; i < n; i++)
+        for (int j = 0; j < n; j++) {
+          const int c = pmod(j - i, n);
+          const int qseg[2] = {c, 2 * n - 1 - c}, kseg[2] = {j, 2 * n - 1 - j};
+          for (int a = 0; a < 2; a++)
+            for (int b = 0; b < 2; b++) add(qseg[a], kseg[b]);
+        }
+      return 2 * n;
+    case TR_SCHED_HYBRID: {
+      const int nodes = n / n_inner;
+      for (int t = 0; t < nodes; t++)
+        for (int i = 0; i < n_inner; i++)
+          for (int nd = 0; nd < nodes; nd++)
+            for (int pp = 0; pp < n_inner; pp++) add(nd * n_inner + pmod(pp - i, n_inner), pmod(nd - t, nodes) * n_inner + pp);
+      return n;
+    }
+    default:
+      return 0;
+  }
 }
 
 constexpr size_t kWsAlign = 256;
@@ -291,6 +343,47 @@ tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* 
         if (st != TR_OK) return st;
       }
     }
+  }
+  return TR_OK;
+}
+
+tr_status tr_ring_attn_sched(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int n_devices, int causal,
+                             int schedule, int n_inner, const tr_tensor* out, const tr_tensor* lse, float scale,
+                             void* hip_stream) {
+  g_err[0] = 0;
+  if (!q || !k || !v || !out || !lse) return fail(TR_ERR_NULL, "a tensor descriptor is NULL");
+  if (n_devices < 1 || n_devices > 4096) return fail(TR_ERR_SHAPE, "n_devices %d out of range [1, 4096]", n_devices);
+  if (schedule < TR_SCHED_TOKENRING || schedule > TR_SCHED_HYBRID) return fail(TR_ERR_UNSUPPORTED, "unknown schedule %d", schedule);
+  if (schedule == TR_SCHED_ZIGZAG && !causal)
+    return fail(TR_ERR_UNSUPPORTED, "the zigzag partition only exists for the causal case");
+  if (schedule == TR_SCHED_HYBRID && (n_inner < 1 || n_devices % n_inner))
+    return fail(TR_ERR_SHAPE, "hybrid schedule: n_inner %d must divide n_devices %d", n_inner, n_devices);
+  const int n_seg = schedule == TR_SCHED_ZIGZAG ? 2 * n_devices : n_devices;
+  if (q->S < 0 || q->S % n_seg) return fail(TR_ERR_SHAPE, "sequence length %lld is not a multiple of %d segments", (long long)q->S, n_seg);
+  if (k->S != q->S || v->S != q->S) return fail(TR_ERR_SHAPE, "q, k, v must have the same sequence length");
+  if (out->dtype != TR_F32) return fail(TR_ERR_DTYPE, "out must be fp32 (it is the merge accumulator)");
+  if (q->D > 0 && !(scale > 0.f)) scale = 1.0f / sqrtf((float)q->D);
+  tr_status st;
+  if ((st = check_tensor("q", q, true, false, 16)) != TR_OK) return st;
+  if ((st = check_tensor("k", k, true, false, 16)) != TR_OK) return st;
+  if ((st = check_tensor("v", v, true, false, 16)) != TR_OK) return st;
+  if ((st = check_tensor("out", out, false, true, 16)) != TR_OK) return st;
+  if ((st = check_tensor("lse", lse, false, true, 4)) != TR_OK) return st;
+  if (out->B != q->B || out->H != q->H || out->S != q->S || out->D != q->D || lse->B != q->B || lse->H != q->H || lse->S != q->S || lse->D != 1)
+    return fail(TR_ERR_SHAPE, "out/lse shape does not match q");
+
+  std::vector<RingStep> steps;
+  build_schedule(schedule, n_devices, n_inner, causal != 0, steps);
+  const int64_t C = q->S / n_seg;
+  std::vector<char> started((size_t)n_seg, 0);  // has this Query segment received its first block?
+  for (const RingStep& s : steps) {
+    const tr_tensor qc = chunk_view(q, s.qs, C), kj = chunk_view(k, s.ks, C), vj = chunk_view(v, s.ks, C);
+    const tr_tensor oc = chunk_view(out, s.qs, C), lc = chunk_view(lse, s.qs, C);
+    const int diag = causal && s.ks == s.qs;
+    // the first block of a Query segment is the accumulator's initial value; later ones are merged in
+    st = attn_common(&qc, &kj, &vj, diag, 0, scale, &oc, &lc, hip_stream, started[(size_t)s.qs] != 0);
+    if (st != TR_OK) return st;
+    started[(size_t)s.qs] = 1;
   }
   return TR_OK;
 }

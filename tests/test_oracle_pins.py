@@ -284,3 +284,69 @@ def test_zigzag_example_from_paper():
     assert sorted(s for pair in seg for s in pair) == list(range(8))
     # balanced causal work: segment s needs s+1 key segments, so each device gets 2N+1 units
     assert all((a + 1) + (b + 1) == 9 for a, b in seg)
+
+
+# ---------------------------------------------------------------- other step orders (Sec. 2.1, 3.3.2, 3.3.3)
+def _causal_pairs(n):
+    return [(c, j) for c in range(n) for j in range(c + 1)]
+
+
+def test_other_orders_cover_every_needed_pair_once():
+    for n in (1, 2, 4, 8):
+        assert sorted(oracle.ring_attention_order(n, False)) == [(c, j) for c in range(n) for j in range(n)]
+        assert sorted(oracle.ring_attention_order(n, True)) == _causal_pairs(n)
+        assert sorted(oracle.zigzag_order(n)) == _causal_pairs(2 * n)
+        for per_node in (d for d in (1, 2, 4, 8) if n % d == 0):
+            assert sorted(oracle.hybrid_order(n // per_node, per_node, False)) == [(c, j) for c in range(n) for j in range(n)]
+            assert sorted(oracle.hybrid_order(n // per_node, per_node, True)) == _causal_pairs(n)
+    # Ring Attention: Query chunk j meets K/V chunks j, j-1, j-2, ... (the K/V ring runs the other way)
+    assert [kv for q, kv in oracle.ring_attention_order(4, False) if q == 1] == [1, 0, 3, 2]
+
+
+def test_hybrid_degenerates_to_its_two_ingredients():
+    for causal in (False, True):
+        # one node: plain Algorithm 1; one device per node: plain Ring Attention
+        assert oracle.hybrid_order(1, 8, causal) == [(c, j) for _, j, c in oracle.ring_schedule(8, causal)]
+        assert oracle.hybrid_order(8, 1, causal) == oracle.ring_attention_order(8, causal)
+    # two nodes of four (the paper's figure): in the first outer step a node only touches its own K/V
+    first = oracle.hybrid_order(2, 4, False)[:32]
+    assert all((q // 4) == (kv // 4) for q, kv in first)
+    assert all((q // 4) != (kv // 4) for q, kv in oracle.hybrid_order(2, 4, False)[32:])
+
+
+def test_zigzag_balances_causal_work_and_releases_queries():
+    n = 4
+    steps = oracle.zigzag_steps(n)
+    work = {}
+    for i, j, qs, ks in steps:                      # a full segment pair is 1 unit, a diagonal one 1/2
+        work[(i, j)] = work.get((i, j), 0.0) + (0.5 if qs == ks else 1.0)
+    assert set(work) == {(i, j) for i in range(n) for j in range(n)} and set(work.values()) == {2.0}
+    # contiguous chunks, by contrast, leave device loads between 1/2 and N - 1/2 units
+    cont = {}
+    for i, j, c in oracle.ring_schedule(n, True):
+        cont[j] = cont.get(j, 0.0) + (0.5 if j == c else 1.0)
+    assert min(cont.values()) == 0.5 and max(cont.values()) == n - 0.5
+    # segment 0's Query is finished after iteration 0 (Sec. 3.3.2: it need not be sent on)
+    assert {i for i, _, qs, _ in steps if qs == 0} == {0}
+    # after iteration 0 a device either uses both Query segments on its first K/V segment or the
+    # late Query segment on both K/V segments
+    for i in range(1, n):
+        for j in range(n):
+            qs_ks = [(qs, ks) for ii, jj, qs, ks in steps if (ii, jj) == (i, j)]
+            c = (j - i) % n
+            expect = [(c, j), (2 * n - 1 - c, j)] if j < c else [(2 * n - 1 - c, j), (2 * n - 1 - c, 2 * n - 1 - j)]
+            assert qs_ks == expect
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_every_order_reaches_unchunked_attention(causal):
+    B, Hq, Hkv, S, D = 1, 2, 1, 32, 8
+    q, k, v = _rand((B, Hq, S, D), 71), _rand((B, Hkv, S, D), 72), _rand((B, Hkv, S, D), 73)
+    ref_o, ref_l = oracle.attention_full(q, k, v, 0.3, causal=causal)
+    orders = {"ring": (8, oracle.ring_attention_order(8, causal)), "hybrid": (8, oracle.hybrid_order(2, 4, causal))}
+    if causal:
+        orders["zigzag"] = (8, oracle.zigzag_order(4))
+    for name, (n_seg, order) in orders.items():
+        o, l = oracle.ring_attention(q, k, v, n_seg, causal, 0.3, order=order)
+        assert np.allclose(o, ref_o, atol=1e-12, rtol=0), name
+        assert np.allclose(l, ref_l, atol=1e-12, rtol=0), name
