@@ -165,13 +165,25 @@ def bench_merge_only(tr, wl, steps, warmup):
         acc_o.zero_(); acc_l.fill_(float("-inf"))
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(cfg.n_partials)]
         for i, (a, b) in enumerate(ev):
-            a.record(); tr.tr_merge(acc_o, acc_l, outs[i], lses[i]); b.record()
+            tr.tr_time_next_kernel(a, b); tr.tr_merge(acc_o, acc_l, outs[i], lses[i])
         torch.cuda.synchronize()
         durations += _event_ms(ev)
     ms = sum(durations) / len(durations)
     gbs = per_call_bytes / (ms * 1e-3) / 1e9
-    return {"workload": "cfg4 merge-only: 8 fp32 partials [1,32,32768,128] in ring order", "ms_per_merge": ms,
-            "bytes_per_merge": per_call_bytes, "gbs": gbs, "frac_hbm_peak": gbs / PEAK_HBM_GBS}
+    res = {"workload": "cfg4 merge-only: 8 fp32 partials [1,32,32768,128] in ring order", "ms_per_merge": ms,
+           "bytes_per_merge": per_call_bytes, "gbs": gbs, "frac_hbm_peak": gbs / PEAK_HBM_GBS,
+           "ms_all_8": ms * cfg.n_partials}
+    # the same eight partials through one tr_merge_n call: each partial read once, result written once
+    nary_bytes = (cfg.n_partials + 1) * (acc_o.numel() + acc_l.numel()) * 4
+    tr.tr_merge_n(acc_o, acc_l, outs, lses)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(max(steps, 3))]
+    for a, b in ev:
+        tr.tr_time_next_kernel(a, b); tr.tr_merge_n(acc_o, acc_l, outs, lses)
+    torch.cuda.synchronize()
+    ms_n = sum(_event_ms(ev)) / len(ev)
+    res["nary"] = {"ms_all_8": ms_n, "bytes": nary_bytes, "gbs": nary_bytes / (ms_n * 1e-3) / 1e9,
+                   "frac_hbm_peak": nary_bytes / (ms_n * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    return res
 
 
 def bench_ring(tr, wl, name, steps, warmup, fused, schedule=None, n_inner=1):

@@ -116,6 +116,24 @@ tr_status tr_merge(const tr_tensor* out_acc, const tr_tensor* lse_acc,
                    const tr_tensor* block_out, const tr_tensor* block_lse, void* hip_stream);
 
 /*
+ * The Update of Sec. 3.1 folded over n partial results in one pass (n-ary merge):
+ *   lse = ln sum_i exp(block_lse_i),   out = sum_i exp(block_lse_i - lse) * block_out_i
+ * (evaluated relative to the largest block_lse).  Because the Update is associative and
+ * commutative this equals n pairwise tr_merge calls up to fp32 rounding, but every partial is
+ * read once and the result written once.
+ *   out [B,H,S,D] fp32, lse [B,H,S] fp32: written; with accumulate != 0 their old contents take
+ *     part as one more partial (read + written), otherwise they need not be initialised.
+ *   block_outs[i] [B,H,S,D] fp32 or bf16 (one dtype for all), block_lses[i] [B,H,S] fp32, i < n,
+ *     1 <= n <= 16: host arrays of n descriptor pointers; all partials share their strides.
+ * A partial row with lse = -inf has weight 0 and its out values are ignored; if every partial
+ * of a row is empty the result is out = 0, lse = -inf.  D multiple of 4 (fp32) or 8 (bf16).
+ * The partials must not overlap out / lse (TR_ERR_ALIAS).
+ */
+tr_status tr_merge_n(const tr_tensor* out, const tr_tensor* lse,
+                     const tr_tensor* const* block_outs, const tr_tensor* const* block_lses,
+                     int n, int accumulate, void* hip_stream);
+
+/*
  * The whole schedule of Algorithm 1 on one GPU, without communication: Q, K, V are split
  * into n_chunks chunks along S; for i in 0..n-1, for j in 0..n-1 the "device" j attends
  * Query chunk c = (j - i) mod n to its K_j, V_j and the block result is merged into

@@ -62,6 +62,8 @@ def _load():
     lib.tr_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
                                   ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
     lib.tr_probe_mfma.restype = ctypes.c_int
+    lib.tr_merge_n.argtypes = [P, P, ctypes.POINTER(P), ctypes.POINTER(P), ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    lib.tr_merge_n.restype = ctypes.c_int
     lib.tr_ring_attn_sched.argtypes = [P, P, P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P, ctypes.c_float,
                                        ctypes.c_void_p]
     lib.tr_ring_attn_sched.restype = ctypes.c_int
@@ -138,6 +140,19 @@ def tr_block_attn_merge(q, k, v, mask_kind, scale, out_acc, lse_acc, stream=None
 def tr_merge(out_acc, lse_acc, block_out, block_lse, stream=None):
     """Out, Lse <- Update(block_out, block_lse), in place on out_acc / lse_acc."""
     _check(_lib.tr_merge(desc(out_acc), desc(lse_acc), desc(block_out), desc(block_lse), _stream(stream)))
+
+
+def tr_merge_n(out, lse, block_outs, block_lses, accumulate=False, stream=None):
+    """out, lse <- n-ary merge of the partial results (plus the old out/lse if accumulate)."""
+    n = len(block_outs)
+    if len(block_lses) != n:
+        raise ValueError("block_outs and block_lses differ in length")
+    P = ctypes.POINTER(TrTensor)
+    bo = [desc(t) for t in block_outs]
+    bl = [desc(t) for t in block_lses]
+    bo_arr = (P * max(n, 1))(*[ctypes.pointer(d) for d in bo])
+    bl_arr = (P * max(n, 1))(*[ctypes.pointer(d) for d in bl])
+    _check(_lib.tr_merge_n(desc(out), desc(lse), bo_arr, bl_arr, n, int(bool(accumulate)), _stream(stream)))
 
 
 def tr_time_next_kernel(start_event, stop_event):

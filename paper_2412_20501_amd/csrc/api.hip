@@ -270,6 +270,58 @@ tr_status tr_merge(const tr_tensor* out_acc, const tr_tensor* lse_acc, const tr_
   return TR_OK;
 }
 
+tr_status tr_merge_n(const tr_tensor* out, const tr_tensor* lse, const tr_tensor* const* block_outs,
+                     const tr_tensor* const* block_lses, int n, int accumulate, void* hip_stream) {
+  g_err[0] = 0;
+  tr_status st;
+  if (!block_outs || !block_lses) return fail(TR_ERR_NULL, "the arrays of partial results must not be NULL");
+  if (n < 1 || n > tr::kMergeNMax) return fail(TR_ERR_SHAPE, "n = %d partials out of range [1, %d]", n, tr::kMergeNMax);
+  if ((st = check_tensor("out", out, false, true, 16)) != TR_OK) return st;
+  if ((st = check_tensor("lse", lse, false, true, 4)) != TR_OK) return st;
+  if (lse->D != 1) return fail(TR_ERR_SHAPE, "lse tensors must have D = 1");
+  if (out->D % 4) return fail(TR_ERR_SHAPE, "D = %lld must be a multiple of 4", (long long)out->D);
+  if (lse->B != out->B || lse->H != out->H || lse->S != out->S) return fail(TR_ERR_SHAPE, "lse shape does not match out");
+  if (overlaps(out, lse)) return fail(TR_ERR_ALIAS, "out and lse overlap");
+  if ((int64_t)out->B * out->H * out->S >= ((int64_t)1 << 32)) return fail(TR_ERR_SHAPE, "too many elements for one launch");
+  const tr_tensor* bo0 = block_outs[0];
+  const tr_tensor* bl0 = block_lses[0];
+  for (int i = 0; i < n; i++) {
+    const tr_tensor* bo = block_outs[i];
+    const tr_tensor* bl = block_lses[i];
+    if ((st = check_tensor("block_out", bo, true, true, 8)) != TR_OK) return st;
+    if (bo->dtype == TR_F32 && (st = check_tensor("block_out", bo, true, true, 16)) != TR_OK) return st;
+    if ((st = check_tensor("block_lse", bl, false, true, 4)) != TR_OK) return st;
+    if (bo->B != out->B || bo->H != out->H || bo->S != out->S || bo->D != out->D) return fail(TR_ERR_SHAPE, "block_out %d: shape does not match out", i);
+    if (bl->B != out->B || bl->H != out->H || bl->S != out->S || bl->D != 1) return fail(TR_ERR_SHAPE, "block_lse %d: shape does not match lse", i);
+    if (bo->dtype != bo0->dtype) return fail(TR_ERR_DTYPE, "block_out %d: all partials must have one dtype", i);
+    if (bo->stride_b != bo0->stride_b || bo->stride_h != bo0->stride_h || bo->stride_s != bo0->stride_s ||
+        bl->stride_b != bl0->stride_b || bl->stride_h != bl0->stride_h || bl->stride_s != bl0->stride_s)
+      return fail(TR_ERR_STRIDE, "partial %d: all partials must share their strides", i);
+    if (bo0->dtype == TR_BF16 && out->D % 8) return fail(TR_ERR_SHAPE, "D = %lld must be a multiple of 8 for bf16 partials", (long long)out->D);
+    if (overlaps(out, bo) || overlaps(out, bl) || overlaps(lse, bo) || overlaps(lse, bl))
+      return fail(TR_ERR_ALIAS, "partial %d overlaps the result tensors", i);
+  }
+
+  tr::MergeNParams p;
+  memset(&p, 0, sizeof(p));
+  p.out = (float*)out->ptr; p.lse = (float*)lse->ptr;
+  for (int i = 0; i < n; i++) { p.blk_out[i] = block_outs[i]->ptr; p.blk_lse[i] = (const float*)block_lses[i]->ptr; }
+  p.o_sb = out->stride_b; p.o_sh = out->stride_h; p.o_ss = out->stride_s;
+  p.l_sb = lse->stride_b; p.l_sh = lse->stride_h; p.l_ss = lse->stride_s;
+  p.bo_sb = bo0->stride_b; p.bo_sh = bo0->stride_h; p.bo_ss = bo0->stride_s;
+  p.bl_sb = bl0->stride_b; p.bl_sh = bl0->stride_h; p.bl_ss = bl0->stride_s;
+  p.B = (int)out->B; p.H = (int)out->H; p.S = (int)out->S; p.D = (int)out->D;
+  p.n = n; p.accumulate = accumulate ? 1 : 0;
+  auto dense = [](const tr_tensor* t) {
+    return t->stride_s == t->D && t->stride_h == t->S * t->D && t->stride_b == t->H * t->S * t->D;
+  };
+  p.contiguous = dense(out) && dense(bo0) && dense(lse) && dense(bl0);
+  if (p.B == 0 || p.H == 0 || p.S == 0 || p.D == 0) return TR_OK;
+  const hipError_t e = tr::launch_merge_n(p, bo0->dtype == TR_BF16, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail(TR_ERR_HIP, "n-ary merge launch failed: %s", hipGetErrorString(e));
+  return TR_OK;
+}
+
 size_t tr_ring_attn_workspace_bytes(const tr_tensor* q, int n_chunks) {
   if (!q || n_chunks < 1 || q->B < 0 || q->H < 0 || q->S < 0 || q->D < 0 || q->S % n_chunks) return 0;
   const size_t C = (size_t)(q->S / n_chunks);

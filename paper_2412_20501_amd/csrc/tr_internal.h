@@ -42,10 +42,28 @@ struct MergeParams {
   int contiguous;  // 1: all four tensors are dense [B*H*S, D] / [B*H*S]
 };
 
+// Arguments of the n-ary merge kernel: up to kMergeNMax partial results with common strides.
+constexpr int kMergeNMax = 16;
+struct MergeNParams {
+  float* out;        // fp32 [B,H,S,D], written (read as one more partial if accumulate)
+  float* lse;        // fp32 [B,H,S]
+  const void* blk_out[kMergeNMax];   // fp32 or bf16
+  const float* blk_lse[kMergeNMax];
+  int64_t o_sb, o_sh, o_ss;
+  int64_t l_sb, l_sh, l_ss;
+  int64_t bo_sb, bo_sh, bo_ss;
+  int64_t bl_sb, bl_sh, bl_ss;
+  int B, H, S, D;
+  int n;           // number of partials
+  int accumulate;  // 1: the old contents of out / lse take part as a further partial
+  int contiguous;  // 1: every tensor is dense [B*H*S, D] / [B*H*S]
+};
+
 // Launchers (defined next to their kernels). They only enqueue; errors come back as hipError_t.
 // epilogue: 0 = bf16 block_out, 1 = fp32 block_out, 2 = merge into the fp32 accumulators p.out / p.lse
 hipError_t launch_block_attn(const AttnParams& p, int D, int epilogue, hipStream_t stream);
 hipError_t launch_merge(const MergeParams& p, bool blk_bf16, hipStream_t stream);
+hipError_t launch_merge_n(const MergeNParams& p, bool blk_bf16, hipStream_t stream);
 int attn_rows_per_block();  // query rows one attention workgroup covers
 // MFMA-only measurement kernel: n_blocks workgroups, each wave issuing 8 * iters MFMAs (32x32x16 bf16)
 hipError_t launch_mfma_probe(const void* operands, float* sink, int iters, int n_blocks, hipStream_t stream);

@@ -25,7 +25,7 @@ def _t(tr, dtype, B, H, S, D, ptr=0x7F0000000000, strides=None):
 def test_every_declared_symbol_is_exported(tr):
     text = open(HEADER).read()
     names = set(re.findall(r"\b(tr_[a-z_]+)\s*\(", text))
-    assert {"tr_block_attn", "tr_block_attn_causal_at", "tr_block_attn_merge", "tr_merge", "tr_ring_attn",
+    assert {"tr_block_attn", "tr_block_attn_causal_at", "tr_block_attn_merge", "tr_merge", "tr_merge_n", "tr_ring_attn", "tr_ring_attn_sched",
             "tr_ring_attn_workspace_bytes", "tr_time_next_kernel", "tr_probe_mfma", "tr_last_error", "tr_version"} <= names
     lib = ctypes.CDLL(tr.LIB_PATH)
     for n in names:
@@ -107,6 +107,35 @@ def test_ring_attn_rejects_bad_arguments_and_workspace_size(tr):
     assert call(nb=need - 1)[0] == 7 and call(ws=ws + 16)[0] == 7 and call(nb=0)[0] == 7      # (ws = NULL selects the fused form)
     st, msg = call(ws=0x7F3000000000)
     assert st == 5 and "workspace" in msg
+
+
+def test_merge_n_and_sched_reject_bad_arguments(tr):
+    lib = tr.raw_lib()
+    B = ctypes.byref
+    P = ctypes.POINTER(tr.TrTensor)
+    o = _t(tr, tr.TR_F32, 1, 2, 64, 128); l = _t(tr, tr.TR_F32, 1, 2, 64, 1, ptr=0x7F1000000000)
+    bo = [_t(tr, tr.TR_F32, 1, 2, 64, 128, ptr=0x7F2000000000 + i * 0x10000000) for i in range(3)]
+    bl = [_t(tr, tr.TR_F32, 1, 2, 64, 1, ptr=0x7F4000000000 + i * 0x10000000) for i in range(3)]
+    arr = lambda ts: (P * len(ts))(*[ctypes.pointer(t) for t in ts])
+    call = lambda o=o, l=l, bo=bo, bl=bl, n=3: _status(tr, lib.tr_merge_n, B(o), B(l), arr(bo), arr(bl), n, 0, None)
+    assert call(n=0)[0] == 3 and call(n=17)[0] == 3
+    assert call(o=_t(tr, tr.TR_BF16, 1, 2, 64, 128))[0] == 2
+    assert call(bo=bo[:2] + [_t(tr, tr.TR_BF16, 1, 2, 64, 128, ptr=0x7F6000000000)])[0] == 2          # mixed dtypes
+    assert call(bo=bo[:2] + [_t(tr, tr.TR_F32, 1, 2, 64, 128, ptr=0x7F6000000000, strides=(2 * 64 * 256, 64 * 256, 256))])[0] == 4
+    assert call(bo=bo[:2] + [_t(tr, tr.TR_F32, 1, 2, 63, 128, ptr=0x7F6000000000)])[0] == 3
+    assert call(bo=bo[:2] + [_t(tr, tr.TR_F32, 1, 2, 64, 128, ptr=0x7F0000000040)])[0] == 5            # aliases out
+    assert lib.tr_merge_n(B(o), B(l), None, arr(bl), 3, 0, None) == 1
+
+    q = _t(tr, tr.TR_BF16, 1, 4, 4096, 128); k = _t(tr, tr.TR_BF16, 1, 4, 4096, 128, ptr=0x7F1000000000)
+    v = _t(tr, tr.TR_BF16, 1, 4, 4096, 128, ptr=0x7F2000000000)
+    oo = _t(tr, tr.TR_F32, 1, 4, 4096, 128, ptr=0x7F3000000000); ll = _t(tr, tr.TR_F32, 1, 4, 4096, 1, ptr=0x7F5000000000)
+    sched = lambda n=8, causal=1, s=0, inner=1, oo=oo: _status(tr, lib.tr_ring_attn_sched, B(q), B(k), B(v), n, causal, s, inner, B(oo), B(ll), 0.0, None)
+    assert sched(s=7)[0] == 6 and sched(s=-1)[0] == 6
+    assert sched(s=tr.TR_SCHED_ZIGZAG, causal=0)[0] == 6                                               # zigzag is causal only
+    assert sched(s=tr.TR_SCHED_HYBRID, inner=3)[0] == 3 and sched(s=tr.TR_SCHED_HYBRID, inner=0)[0] == 3
+    assert sched(n=0)[0] == 3 and sched(n=3)[0] == 3                                                   # 4096 % 3
+    assert sched(n=24, s=tr.TR_SCHED_ZIGZAG)[0] == 3                                                   # 4096 % 48
+    assert sched(oo=_t(tr, tr.TR_BF16, 1, 4, 4096, 128, ptr=0x7F3000000000))[0] == 2
 
 
 def test_probe_rejects_bad_arguments(tr):

@@ -70,3 +70,24 @@ def test_config4_merge_full_size_sampled_rows(lib):
     assert not torch.isnan(acc_o).any() and not torch.isnan(acc_l).any()
     for l in lses:
         assert torch.all(acc_l >= torch.from_numpy(l).to("cuda"))
+
+
+def test_config4_merge_n_full_size_sampled_rows(lib):
+    """The same eight partials merged by one tr_merge_n call (each read once); oracle on sampled rows."""
+    cfg = wl.CONFIGS["cfg4_merge"]
+    outs, lses = wl.make_merge_partials(cfg)
+    dev_o = [torch.from_numpy(o).to("cuda") for o in outs]
+    dev_l = [torch.from_numpy(l).to("cuda") for l in lses]
+    out = torch.full((cfg.B, cfg.H, cfg.S, cfg.D), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((cfg.B, cfg.H, cfg.S), float("nan"), dtype=torch.float32, device="cuda")
+    lib.tr_merge_n(out, lse, dev_o, dev_l)
+    torch.cuda.synchronize()
+    rows = wl.sample_rows(cfg.S, 4096, 512, seed=cfg.seed + 1)
+    ref_o, ref_l = oracle.merge_nary([o[:, :, rows] for o in outs], [l[:, :, rows] for l in lses])
+    ridx = torch.from_numpy(rows).to("cuda")
+    d_o, d_l = max_abs(to_np(out[:, :, ridx]), ref_o), max_abs(to_np(lse[:, :, ridx]), ref_l)
+    print(f"cfg4 n-ary: {len(rows)} rows x {cfg.H} heads, max|d out| {d_o:.3e}, max|d lse| {d_l:.3e}")
+    assert d_o <= MERGE_TOL and d_l <= MERGE_TOL
+    assert not torch.isnan(out).any() and not torch.isnan(lse).any()
+    for l in dev_l:
+        assert torch.all(lse >= l)

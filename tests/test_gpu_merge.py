@@ -100,3 +100,69 @@ def test_merge_config4_downscaled_ring_order_and_any_order(lib):
             lib.tr_merge(acc_o, acc_l, _dev(outs[i]), _dev(lses[i]))
         torch.cuda.synchronize()
         assert max_abs(to_np(acc_o), ref_o) <= TOL and max_abs(to_np(acc_l), ref_l) <= TOL
+
+
+# ---------------------------------------------------------------- n-ary merge (the Update folded over n partials)
+def _bf16_round(x):
+    return wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(x))
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 8, 16])
+@pytest.mark.parametrize("shape,bf16", [((1, 2, 77, 128), False), ((2, 3, 130, 64), True), ((1, 5, 1000, 36), False), ((1, 2, 33, 40), True)])
+@pytest.mark.parametrize("accumulate", [False, True])
+def test_merge_n_matches_oracle(lib, n, shape, bf16, accumulate):
+    B, H, S, D = shape
+    rng = np.random.default_rng(100 + n)
+    outs = [rng.standard_normal(shape).astype(np.float32) for _ in range(n)]
+    if bf16:
+        outs = [_bf16_round(o) for o in outs]
+    lses = [rng.uniform(-5, 15, (B, H, S)).astype(np.float32) for _ in range(n)]
+    for i in range(n):                                      # sprinkle empty rows; row 0 is empty everywhere
+        lses[i][rng.random((B, H, S)) < 0.1] = -np.inf
+        lses[i][:, :, 0] = -np.inf
+        outs[i][np.isneginf(lses[i])] = np.nan if not bf16 else 0.0   # garbage that must not leak
+    old_o = rng.standard_normal(shape).astype(np.float32)
+    old_l = rng.uniform(-5, 15, (B, H, S)).astype(np.float32)
+    old_l[:, :, 0] = -np.inf
+    out, lse = (_dev(old_o), _dev(old_l)) if accumulate else (torch.full(shape, float("nan"), device="cuda"), torch.full((B, H, S), float("nan"), device="cuda"))
+    dev_o = [(_dev(o).to(torch.bfloat16) if bf16 else _dev(o)) for o in outs]
+    lib.tr_merge_n(out, lse, dev_o, [_dev(l) for l in lses], accumulate)
+    torch.cuda.synchronize()
+    clean = [np.where(np.isneginf(l)[..., None], 0.0, o) for o, l in zip(outs, lses)]
+    ref_o, ref_l = oracle.merge_nary(clean + ([old_o] if accumulate else []), lses + ([old_l] if accumulate else []))
+    o, l = to_np(out), to_np(lse)
+    assert not np.isnan(o).any() and not np.isnan(l).any()
+    assert max_abs(o, ref_o) <= TOL and max_abs(l, ref_l) <= TOL
+    assert np.all(o[:, :, 0] == 0) and np.all(np.isneginf(l[:, :, 0]))       # all partials empty: identity element
+
+
+def test_merge_n_agrees_with_pairwise_updates(lib):
+    """Folding tr_merge over the partials (Algorithm 1's way) and the one-pass form agree to rounding."""
+    B, H, S, D, n = 1, 4, 300, 128, 8
+    rng = np.random.default_rng(7)
+    outs = [_dev(rng.standard_normal((B, H, S, D)).astype(np.float32)) for _ in range(n)]
+    lses = [_dev(rng.uniform(-5, 15, (B, H, S)).astype(np.float32)) for _ in range(n)]
+    acc_o = torch.zeros((B, H, S, D), device="cuda"); acc_l = torch.full((B, H, S), float("-inf"), device="cuda")
+    for o, l in zip(outs, lses):
+        lib.tr_merge(acc_o, acc_l, o, l)
+    one_o = torch.empty_like(acc_o); one_l = torch.empty_like(acc_l)
+    lib.tr_merge_n(one_o, one_l, outs, lses)
+    torch.cuda.synchronize()
+    assert max_abs(to_np(one_o), to_np(acc_o)) <= TOL and max_abs(to_np(one_l), to_np(acc_l)) <= TOL
+
+
+def test_merge_n_argument_errors(lib):
+    o = torch.zeros((1, 2, 8, 16), device="cuda"); l = torch.zeros((1, 2, 8), device="cuda")
+    b = [torch.zeros((1, 2, 8, 16), device="cuda") for _ in range(17)]; bl = [torch.zeros((1, 2, 8), device="cuda") for _ in range(17)]
+    with pytest.raises(lib.TokenRingError, match="out of range"):
+        lib.tr_merge_n(o, l, b, bl)
+    with pytest.raises(lib.TokenRingError, match="out of range"):
+        lib.tr_merge_n(o, l, [], [])
+    with pytest.raises(lib.TokenRingError, match="overlaps"):
+        lib.tr_merge_n(o, l, [b[0], o], [bl[0], bl[1]])
+    with pytest.raises(lib.TokenRingError, match="one dtype"):
+        lib.tr_merge_n(o, l, [b[0], b[1].to(torch.bfloat16)], bl[:2])
+    with pytest.raises(lib.TokenRingError, match="share their strides"):
+        lib.tr_merge_n(o, l, [b[0], torch.zeros((1, 2, 8, 32), device="cuda")[..., :16]], bl[:2])
+    with pytest.raises(lib.TokenRingError, match="shape"):
+        lib.tr_merge_n(o, l, [b[0], torch.zeros((1, 2, 9, 16), device="cuda")], bl[:2])
