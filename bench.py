@@ -313,6 +313,7 @@ def main():
             "ring_cfg3_zigzag": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True, schedule=tr.TR_SCHED_ZIGZAG),
             "ring_cfg3_hybrid_2x4": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True, schedule=tr.TR_SCHED_HYBRID, n_inner=4),
             "ring_cfg5": bench_ring(tr, wl, "cfg5_gqa", 2, 1, fused=True),
+            "ring_dit": bench_ring(tr, wl, "dit_ring", ex_steps, 1, fused=True),
         }
         torch.cuda.empty_cache()
     if not args.no_cpu_baseline:

@@ -122,6 +122,23 @@ def test_ring_config3_causal_32k_8_chunks_sampled_rows(lib):
     assert worst_o <= OUT_TOL and worst_l <= LSE_TOL
 
 
+def test_ring_dit_shape_noncausal_d64_sampled_rows(lib):
+    """Non-causal, head dim 64, batch 2, four devices (the diffusion-transformer case study): batch 0 is checked."""
+    cfg = wl.CONFIGS["dit_ring"]
+    qb, kb, vb = wl.make_qkv_bits(cfg)
+    out, lse = _ring(lib, bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb), cfg.n_chunks, cfg.causal, cfg.scale)
+    assert not torch.isnan(out).any() and not torch.isnan(lse).any()
+    worst_o, worst_l, n = _check_rows(cfg, out, lse, qb, kb, vb, n_random=64)
+    print(f"dit: {n} rows x {cfg.Hq} heads, max|d out| {worst_o:.3e}, max|d lse| {worst_l:.3e}")
+    assert worst_o <= OUT_TOL and worst_l <= LSE_TOL
+    # second batch entry: a few heads
+    rows = wl.sample_rows(cfg.S, cfg.chunk, 16, seed=cfg.seed + 2)
+    ridx = torch.from_numpy(rows).to("cuda")
+    for h in (0, 11, 23):
+        ref_o, ref_l = oracle.attention_rows(f64(qb[1, h][rows]), rows, f64(kb[1, h]), f64(vb[1, h]), cfg.scale, False)
+        assert max_abs(to_np(out[1, h][ridx]), ref_o) <= OUT_TOL and max_abs(to_np(lse[1, h][ridx]), ref_l) <= LSE_TOL
+
+
 def test_ring_config5_gqa_128k_16_chunks_sampled_rows(lib):
     cfg = wl.CONFIGS["cfg5_gqa"]
     qb, kb, vb = wl.make_qkv_bits(cfg)

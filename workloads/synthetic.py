@@ -67,6 +67,8 @@ CONFIGS = {
     "cfg4_merge": MergeConfig("cfg4_merge", 1, 32, 32768, 128, 8, -5.0, 15.0, 20505),
     # GQA long context, 32 query heads / 8 KV heads, seq 131072 as 16 chunks of 8192: 136 steps
     "cfg5_gqa": AttnConfig("cfg5_gqa", 1, 32, 8, 131072, 128, 16, True, 0.5, 20506),
+    # diffusion-transformer shaped: long non-causal sequence, head dim 64, batch 2, four devices (Sec. 3.3.1)
+    "dit_ring": AttnConfig("dit_ring", 2, 24, 24, 16384, 64, 4, False, 1.0, 20507),
 }
 
 
