@@ -7,8 +7,8 @@ followed by tr_merge of that block into the fp32 accumulators.  `value` is the s
 attention TFLOP (4*Sq*Sk*D per head) divided by the whole step time, inputs resident in
 HBM.  `roofline` is the block-attention kernel against the bf16 MFMA peak, from HIP-event
 durations recorded around every launch of the timed region; `merge_roofline` is the same
-for the merge kernel against HBM.  `extras` adds the merge-only bandwidth workload and the
-two ring-schedule workloads.  `cpu_baseline` times the fp64 oracle on a few heads of the
+for the merge kernel against HBM.  `extras` adds an MFMA-only ceiling measurement, the fused
+step, the merge-only bandwidth workload (pairwise and n-ary) and the ring-schedule workloads.  `cpu_baseline` times the fp64 oracle on a few heads of the
 same block step on the host cores.
 """
 import argparse
@@ -23,6 +23,11 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# HBM bytes per launch of the two kernels of the cfg2 step, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# summarised in profiles/block_step_cfg2_block_attn_and_merge.md (KiB per dispatch; FETCH_SIZE scaled by the 2.0 that a
+# plain 1 GiB copy calibrates, WRITE_SIZE by 1.0).  Counters cannot be read from inside this process.
+TRAFFIC_ATTN_BYTES = (82123 * 2 + 33280) * 1024
+TRAFFIC_MERGE_BYTES = (51230 * 2 + 66048) * 1024
 
 
 def _dev(bits):
@@ -295,11 +300,11 @@ def main():
                    "seed": cfg.seed, "scale": cfg.scale},
         "roofline": {"bound": "mfma", "kernel": "block_attn_kernel<128,bf16 out>", "achieved": r["attn_tflops"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": r["attn_tflops"] / PEAK_BF16_TFLOPS,
-                     "traffic": None, "ms_avg": r["attn_ms_avg"], "ms_min": r["attn_ms_min"],
+                     "traffic": TRAFFIC_ATTN_BYTES, "ms_avg": r["attn_ms_avg"], "ms_min": r["attn_ms_min"],
                      "flops_per_launch": r["flops"]},
         "merge_roofline": {"bound": "hbm", "kernel": "merge_kernel<bf16 block>", "achieved": r["merge_gbs"],
                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": r["merge_gbs"] / PEAK_HBM_GBS,
-                           "traffic": None, "ms_avg": r["merge_ms_avg"], "bytes_per_launch": r["merge_bytes"]},
+                           "traffic": TRAFFIC_MERGE_BYTES, "ms_avg": r["merge_ms_avg"], "bytes_per_launch": r["merge_bytes"]},
     }
     if not args.no_extras:
         ex_steps = max(3, min(args.steps, 10))
