@@ -89,6 +89,35 @@ def bench_block_step(tr, wl, steps, warmup):
     }
 
 
+def bench_ring_small(tr, wl):
+    """cfg1 (launch-bound correctness workload, 16 block steps of 64 x 64): time only, eager launches and as a HIP graph."""
+    import torch
+    cfg = wl.CONFIGS["cfg1_small"]
+    qb, kb, vb = wl.make_qkv_bits(cfg)
+    q, k, v = _dev(qb), _dev(kb), _dev(vb)
+    out = torch.empty((cfg.B, cfg.Hq, cfg.S, cfg.D), dtype=torch.float32, device="cuda")
+    lse = torch.empty((cfg.B, cfg.Hq, cfg.S), dtype=torch.float32, device="cuda")
+    run = lambda: tr.tr_ring_attn(q, k, v, cfg.n_chunks, cfg.causal, out, lse, cfg.scale, None)
+
+    def timed(fn, n=200):
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e6 / n
+
+    eager_us = timed(run)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    graph_us = timed(graph.replay)
+    return {"workload": "cfg1: B1 H2 S256 D64 as 4 chunks, non-causal, 16 block steps (launch-bound)",
+            "us_eager": eager_us, "us_graph_replay": graph_us}
+
+
 def bench_mfma_ceiling(tr, wl):
     """MFMA-only kernel on operands drawn like the workload's (N(0,1), bf16), every CU busy: what the matrix
     cores sustain on this chip for such data, for comparison with the attention kernel's rate."""
@@ -313,6 +342,7 @@ def main():
             "step_fused": bench_step_fused(tr, wl, ex_steps, 2),
             "block_diag": bench_block_diag(tr, wl, ex_steps, 2),
             "merge_only": bench_merge_only(tr, wl, 3, 1),
+            "ring_cfg1": bench_ring_small(tr, wl),
             "ring_cfg3": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True),
             "ring_cfg3_two_kernel": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=False),
             "ring_cfg3_zigzag": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True, schedule=tr.TR_SCHED_ZIGZAG),

@@ -62,9 +62,23 @@ tr_status check_tensor(const char* name, const tr_tensor* t, bool allow_bf16, bo
   return TR_OK;
 }
 
+// One block step of a schedule: Query segment qs attends K/V segment ks (equal segments of S).
+struct RingStep { int qs, ks; };
+
+// Several block steps of one shape for a single launch: the tensors handed to attn_common are
+// the views of segment 0 (length seg_len along S); step i works on Query segment steps[i].qs
+// and K/V segment steps[i].ks, masked diagonally iff `causal` and both are equal.
+struct StepGroup {
+  const RingStep* steps;
+  int n;
+  int64_t seg_len;
+  bool causal;
+};
+
 // fuse_update: out/lse are fp32 accumulators and the block is merged into them by the kernel's epilogue
 tr_status attn_common(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int causal, int64_t off64, float scale,
-                      const tr_tensor* out, const tr_tensor* lse, void* stream, bool fuse_update = false) {
+                      const tr_tensor* out, const tr_tensor* lse, void* stream, bool fuse_update = false,
+                      const StepGroup* group = nullptr) {
   tr_status st;
   if ((st = check_tensor("q", q, true, false, 16)) != TR_OK) return st;
   if ((st = check_tensor("k", k, true, false, 16)) != TR_OK) return st;
@@ -100,6 +114,23 @@ tr_status attn_common(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v
   const int bm = tr::attn_rows_per_block();
   p.n_qtiles = (p.Sq + bm - 1) / bm;
   p.xcd_map = (p.B * p.Hkv) % 8 == 0 && (int64_t)p.n_qtiles * p.B * p.Hq >= 8;
+  p.n_prob = 1;
+  p.blocks_per_prob = p.n_qtiles * p.B * p.Hq;
+  p.causal_bits = p.causal ? 1u : 0u;
+  if (group) {
+    if (group->n < 1 || group->n > tr::kAttnGroupMax) return fail(TR_ERR_SHAPE, "internal: %d steps in one launch", group->n);
+    p.n_prob = group->n;
+    p.causal = 0; p.causal_off = 0; p.causal_bits = 0;
+    p.q_seg_elems = group->seg_len * q->stride_s; p.k_seg_elems = group->seg_len * k->stride_s;
+    p.v_seg_elems = group->seg_len * v->stride_s; p.o_seg_elems = group->seg_len * out->stride_s;
+    p.l_seg_elems = group->seg_len * lse->stride_s;
+    for (int i = 0; i < group->n; i++) {
+      p.q_seg[i] = (short)group->steps[i].qs;
+      p.k_seg[i] = (short)group->steps[i].ks;
+      if (group->causal && group->steps[i].qs == group->steps[i].ks) p.causal_bits |= 1u << i;
+    }
+  }
+  if ((int64_t)p.blocks_per_prob * p.n_prob >= ((int64_t)1 << 31)) return fail(TR_ERR_SHAPE, "too many workgroups for one launch");
   if (p.B == 0 || p.Hq == 0 || p.Sq == 0) return TR_OK;
   const int epilogue = fuse_update ? 2 : (out->dtype == TR_F32 ? 1 : 0);
   const hipError_t e = tr::launch_block_attn(p, (int)q->D, epilogue, (hipStream_t)stream);
@@ -114,9 +145,6 @@ tr_tensor chunk_view(const tr_tensor* t, int64_t c, int64_t C) {
   r.S = C;
   return r;
 }
-
-// One block step of a schedule: Query segment qs attends K/V segment ks (equal segments of S).
-struct RingStep { int qs, ks; };
 
 inline int pmod(int a, int n) { return ((a % n) + n) % n; }
 
@@ -163,6 +191,37 @@ int build_schedule(int schedule, int n, int n_inner, bool causal, std::vector<Ri
     default:
       return 0;
   }
+}
+
+// Runs the steps in order with the Update fused into the attention epilogue.  Consecutive steps
+// that touch distinct Query segments and are of one kind (first block of their segment, which
+// is written, or a later block, which is merged) are independent of each other - they are what
+// different devices compute at the same time - and go out as one launch.
+tr_status run_steps_fused(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, const tr_tensor* out, const tr_tensor* lse,
+                          int n_seg, bool causal, float scale, const std::vector<RingStep>& steps, void* stream) {
+  const int64_t C = q->S / n_seg;
+  const tr_tensor q0 = chunk_view(q, 0, C), k0 = chunk_view(k, 0, C), v0 = chunk_view(v, 0, C);
+  const tr_tensor o0 = chunk_view(out, 0, C), l0 = chunk_view(lse, 0, C);
+  std::vector<char> started((size_t)n_seg, 0);  // has this Query segment received its first block?
+  std::vector<int> in_group((size_t)n_seg, -1); // index of the group that last used the segment
+  size_t pos = 0;
+  int group_id = 0;
+  while (pos < steps.size()) {
+    const bool merge = started[(size_t)steps[pos].qs] != 0;
+    size_t end = pos;
+    while (end < steps.size() && (int)(end - pos) < tr::kAttnGroupMax && (started[(size_t)steps[end].qs] != 0) == merge &&
+           in_group[(size_t)steps[end].qs] != group_id) {
+      in_group[(size_t)steps[end].qs] = group_id;
+      end++;
+    }
+    const StepGroup g = {steps.data() + pos, (int)(end - pos), C, causal};
+    const tr_status st = attn_common(&q0, &k0, &v0, 0, 0, scale, &o0, &l0, stream, merge, &g);
+    if (st != TR_OK) return st;
+    for (size_t i = pos; i < end; i++) started[(size_t)steps[i].qs] = 1;
+    pos = end;
+    group_id++;
+  }
+  return TR_OK;
 }
 
 constexpr size_t kWsAlign = 256;
@@ -373,7 +432,16 @@ tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* 
       return fail(TR_ERR_ALIAS, "workspace overlaps a tensor argument");
   }
 
+  if (overlaps(out, q) || overlaps(out, k) || overlaps(out, v) || overlaps(lse, q) || overlaps(lse, k) || overlaps(lse, v) || overlaps(out, lse))
+    return fail(TR_ERR_ALIAS, "outputs overlap inputs or each other");
+  if (n_chunks > 8192) return fail(TR_ERR_SHAPE, "n_chunks %d too large (at most 8192)", n_chunks);
+
   // Algorithm 1 replayed on one device: iteration i, "device" j, Query chunk c = (j - i) mod n.
+  if (fused) {
+    std::vector<RingStep> steps;
+    build_schedule(TR_SCHED_TOKENRING, n_chunks, 1, causal != 0, steps);
+    return run_steps_fused(q, k, v, out, lse, n_chunks, causal != 0, scale, steps, hip_stream);
+  }
   for (int i = 0; i < n_chunks; i++) {
     for (int j = 0; j < n_chunks; j++) {
       const int c = ((j - i) % n_chunks + n_chunks) % n_chunks;
@@ -384,9 +452,6 @@ tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* 
       if (i == 0) {
         // first block of Query chunk c: it *is* the accumulator's initial value
         st = attn_common(&qc, &kj, &vj, diag, 0, scale, &oc, &lc, hip_stream);
-        if (st != TR_OK) return st;
-      } else if (fused) {
-        st = attn_common(&qc, &kj, &vj, diag, 0, scale, &oc, &lc, hip_stream, true);
         if (st != TR_OK) return st;
       } else {
         st = attn_common(&qc, &kj, &vj, diag, 0, scale, &ws_out, &ws_lse, hip_stream);
@@ -424,20 +489,11 @@ tr_status tr_ring_attn_sched(const tr_tensor* q, const tr_tensor* k, const tr_te
   if (out->B != q->B || out->H != q->H || out->S != q->S || out->D != q->D || lse->B != q->B || lse->H != q->H || lse->S != q->S || lse->D != 1)
     return fail(TR_ERR_SHAPE, "out/lse shape does not match q");
 
+  if (overlaps(out, q) || overlaps(out, k) || overlaps(out, v) || overlaps(lse, q) || overlaps(lse, k) || overlaps(lse, v) || overlaps(out, lse))
+    return fail(TR_ERR_ALIAS, "outputs overlap inputs or each other");
   std::vector<RingStep> steps;
   build_schedule(schedule, n_devices, n_inner, causal != 0, steps);
-  const int64_t C = q->S / n_seg;
-  std::vector<char> started((size_t)n_seg, 0);  // has this Query segment received its first block?
-  for (const RingStep& s : steps) {
-    const tr_tensor qc = chunk_view(q, s.qs, C), kj = chunk_view(k, s.ks, C), vj = chunk_view(v, s.ks, C);
-    const tr_tensor oc = chunk_view(out, s.qs, C), lc = chunk_view(lse, s.qs, C);
-    const int diag = causal && s.ks == s.qs;
-    // the first block of a Query segment is the accumulator's initial value; later ones are merged in
-    st = attn_common(&qc, &kj, &vj, diag, 0, scale, &oc, &lc, hip_stream, started[(size_t)s.qs] != 0);
-    if (st != TR_OK) return st;
-    started[(size_t)s.qs] = 1;
-  }
-  return TR_OK;
+  return run_steps_fused(q, k, v, out, lse, n_seg, causal != 0, scale, steps, hip_stream);
 }
 
 }  // extern "C"

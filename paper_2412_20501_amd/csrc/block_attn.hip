@@ -27,6 +27,8 @@
 // 64-key tile hands ring slots over.
 #include <type_traits>
 
+#include <atomic>
+
 #include "tr_internal.h"
 
 namespace tr {
@@ -147,8 +149,14 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in an SGPR
   const int ql = lane & 31, hf = lane >> 5;
 
+  // which of the launch's block steps this workgroup belongs to (wave-uniform)
+  const int prob = p.n_prob > 1 ? (int)(blockIdx.x / (unsigned)p.blocks_per_prob) : 0;
+  const int bid = p.n_prob > 1 ? (int)(blockIdx.x - (unsigned)prob * (unsigned)p.blocks_per_prob) : (int)blockIdx.x;
+  const int64_t qseg = p.q_seg[prob], kseg = p.k_seg[prob];
+  const bool causal = (p.causal_bits >> prob) & 1u;
+
   int qt, bh;
-  decode_block(p, blockIdx.x, qt, bh);
+  decode_block(p, bid, qt, bh);
   const int b = bh / p.Hq, hq = bh % p.Hq, hk = hq / (p.Hq / p.Hkv);
   const int q0 = qt * kBM, qw0 = q0 + wave * 32;
   const int qrow = qw0 + ql;
@@ -157,7 +165,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   // Q^T fragments: lane (q, hf) holds Q[q][16*ks + 8*hf .. +7] for every k-step.
   bf16x8 qf[KS];
   {
-    const __bf16* qp = p.q + (int64_t)b * p.q_sb + (int64_t)hq * p.q_sh + (int64_t)qrow_ld * p.q_ss;
+    const __bf16* qp = p.q + qseg * p.q_seg_elems + (int64_t)b * p.q_sb + (int64_t)hq * p.q_sh + (int64_t)qrow_ld * p.q_ss;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks + 8 * hf);
   }
@@ -165,12 +173,12 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   // Key range of this workgroup (in 64-key tiles) and of this wave (in 32-key sub-tiles).
   const int q_last_wg = min(q0 + kBM, p.Sq) - 1;
   int kv_end = p.Sk;
-  if (p.causal) kv_end = max(0, min(p.Sk, q_last_wg + p.causal_off + 1));
+  if (causal) kv_end = max(0, min(p.Sk, q_last_wg + p.causal_off + 1));
   const int n_tiles = (kv_end + kBN - 1) / kBN;
   int wave_kv_end = 0;
   if (qw0 < p.Sq) {
     wave_kv_end = p.Sk;
-    if (p.causal) wave_kv_end = max(0, min(p.Sk, min(qw0 + 31, p.Sq - 1) + p.causal_off + 1));
+    if (causal) wave_kv_end = max(0, min(p.Sk, min(qw0 + 31, p.Sq - 1) + p.causal_off + 1));
   }
   const int jw = (wave_kv_end + SUB - 1) / SUB;  // sub-tiles this wave has visible keys in
   // wave-uniform loop bounds, forced into scalar registers so that every per-step test is one compare
@@ -178,11 +186,11 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   const int jw_odd = __builtin_amdgcn_readfirstlane(min(jw, 2 * n_tiles - 1));     // last odd step index allowed
   // a sub-tile starting at kstart needs masking iff kstart > kmask_from
   int kmask_from_v = p.Sk - SUB;
-  if (p.causal) kmask_from_v = min(kmask_from_v, qw0 + p.causal_off - SUB + 1);
+  if (causal) kmask_from_v = min(kmask_from_v, qw0 + p.causal_off - SUB + 1);
   const int kmask_from = __builtin_amdgcn_readfirstlane(kmask_from_v);
 
-  const __bf16* kg = p.k + (int64_t)b * p.k_sb + (int64_t)hk * p.k_sh;
-  const __bf16* vg = p.v + (int64_t)b * p.v_sb + (int64_t)hk * p.v_sh;
+  const __bf16* kg = p.k + kseg * p.k_seg_elems + (int64_t)b * p.k_sb + (int64_t)hk * p.k_sh;
+  const __bf16* vg = p.v + kseg * p.v_seg_elems + (int64_t)b * p.v_sb + (int64_t)hk * p.v_sh;
 
   // Direct global -> LDS staging (no VGPRs, no ds_write): one wave-wide instruction deposits
   // lane l's 16 bytes at lds_base + 16*l, i.e. RPI consecutive tile rows.  The swizzle is
@@ -316,7 +324,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
 
     if (kstart > kmask_from) {  // some key of the sub-tile is past Sk or above this wave's first diagonal
       int limit = p.Sk - 1;
-      if (p.causal) limit = min(limit, qrow + p.causal_off);
+      if (causal) limit = min(limit, qrow + p.causal_off);
 #pragma unroll
       for (int i = 0; i < 16; i++) {
         const int key = kstart + 8 * (i >> 2) + 4 * hf + (i & 3);
@@ -509,11 +517,11 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   if (hf == 0) my_lse[ql] = lse_blk;
   __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the wave's own LDS writes are visible to all its lanes
   if (EPI != kEpiMerge && hf == 0 && qrow < p.Sq)
-    p.lse[(int64_t)b * p.l_sb + (int64_t)hq * p.l_sh + (int64_t)qrow * p.l_ss] = lse_blk;
+    p.lse[qseg * p.l_seg_elems + (int64_t)b * p.l_sb + (int64_t)hq * p.l_sh + (int64_t)qrow * p.l_ss] = lse_blk;
   const int rr = lane / CPRF, cc = lane % CPRF;
   constexpr int NIT = 32 / RPI_OUT;
-  const int64_t o_bh = (int64_t)b * p.o_sb + (int64_t)hq * p.o_sh + 4 * cc;
-  const int64_t l_bh = (int64_t)b * p.l_sb + (int64_t)hq * p.l_sh;
+  const int64_t o_bh = qseg * p.o_seg_elems + (int64_t)b * p.o_sb + (int64_t)hq * p.o_sh + 4 * cc;
+  const int64_t l_bh = qseg * p.l_seg_elems + (int64_t)b * p.l_sb + (int64_t)hq * p.l_sh;
   if (EPI == kEpiMerge) {
     // Out, Lse <- Update(block_out, block_lse) on the accumulators p.out / p.lse.  All of the
     // wave's accumulator rows are fetched first (the O registers are free by now), so their
@@ -568,12 +576,18 @@ hipError_t launch_one(const AttnParams& p, dim3 grid, hipStream_t stream) {
   constexpr int epi_bytes = kWaves * 32 * 4 * D + kWaves * 32 * 4;
   constexpr int lds_bytes = ring_bytes > epi_bytes ? ring_bytes : epi_bytes;
   static_assert(lds_bytes <= 160 * 1024, "LDS budget of one CU exceeded");
-  static bool attr_set = false;  // raising the dynamic-LDS limit is a per-function, per-process setting
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&block_attn_kernel<D, EPI>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  // Raising the dynamic-LDS limit is a per-function, per-device setting: done once for each
+  // device this process launches on (the flags are atomics, a repeated set is harmless).
+  constexpr int kMaxDevices = 64;
+  static std::atomic<bool> attr_set[kMaxDevices];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices || !attr_set[dev].load(std::memory_order_acquire)) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&block_attn_kernel<D, EPI>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    if (dev >= 0 && dev < kMaxDevices) attr_set[dev].store(true, std::memory_order_release);
   }
   return launch_kernel(block_attn_kernel<D, EPI>, grid, dim3(kThreads), lds_bytes, stream, p);
 }
@@ -581,7 +595,7 @@ hipError_t launch_one(const AttnParams& p, dim3 grid, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_block_attn(const AttnParams& p, int D, int epilogue, hipStream_t stream) {
-  const int64_t nblocks = (int64_t)p.n_qtiles * p.B * p.Hq;
+  const int64_t nblocks = (int64_t)p.n_qtiles * p.B * p.Hq * p.n_prob;
   if (nblocks == 0) return hipSuccess;
   dim3 grid((unsigned)nblocks);
   if (D == 128) {

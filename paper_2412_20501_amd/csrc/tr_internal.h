@@ -8,6 +8,8 @@
 
 namespace tr {
 
+constexpr int kAttnGroupMax = 32;  // block steps one attention launch can carry
+
 // Arguments of the block-attention kernel: raw pointers, element strides, sizes.
 struct AttnParams {
   const __bf16* q;
@@ -26,6 +28,16 @@ struct AttnParams {
   float scale;    // softmax scale (natural units)
   int n_qtiles;   // ceil(Sq / rows per workgroup)
   int xcd_map;    // 1: place all query tiles of a K/V head on one XCD
+  // Several independent block steps of equal shape in one launch (the steps different "devices"
+  // run in the same iteration of a schedule): problem g = blockIdx / blocks_per_prob works on the
+  // Query segment q_seg[g] (q, out, lse advanced by q_seg[g] * *_seg elements) and the K/V
+  // segment k_seg[g], with the causal rule iff bit g of causal_bits is set.  n_prob = 1 with
+  // q_seg[0] = k_seg[0] = 0 and causal_bits = causal is the plain single step.
+  int n_prob;
+  int blocks_per_prob;
+  unsigned causal_bits;
+  int64_t q_seg_elems, k_seg_elems, v_seg_elems, o_seg_elems, l_seg_elems;
+  short q_seg[kAttnGroupMax], k_seg[kAttnGroupMax];
 };
 
 // Arguments of the merge kernel.
