@@ -548,23 +548,33 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
         if (cc == 0) p.lse[l_bh + (int64_t)grow * p.l_ss] = pl.new_lse;
       }
     }
-  } else {
+  } else if (EPI == kEpiF32) {
 #pragma unroll
     for (int it = 0; it < NIT; it++) {
       const int r = it * RPI_OUT + rr;
       const int grow = qw0 + r;
       const f32x4 o = *reinterpret_cast<const f32x4*>(my + r * ROWB + ((cc ^ (r & 15)) << 4));
-      if (grow < p.Sq) {
-        const int64_t oidx = o_bh + (int64_t)grow * p.o_ss;
-        if (EPI == kEpiBf16) {
-          bf16x4 ob;
+      if (grow < p.Sq) *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + o_bh + (int64_t)grow * p.o_ss) = o;
+    }
+  } else {
+    // bf16 rows are half as long: a lane converts two neighbouring chunks and stores 16 bytes
+    constexpr int LPR = D / 8;          // lanes per bf16 row
+    constexpr int RPI_B = 64 / LPR;     // rows one wave-wide store covers
+    const int rb = lane / LPR, cb = lane % LPR;
+    const int64_t ob_bh = qseg * p.o_seg_elems + (int64_t)b * p.o_sb + (int64_t)hq * p.o_sh + 8 * cb;
 #pragma unroll
-          for (int k = 0; k < 4; k++) ob[k] = (__bf16)o[k];
-          *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(p.out) + oidx) = ob;
-        } else {
-          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + oidx) = o;
-        }
+    for (int it = 0; it < 32 / RPI_B; it++) {
+      const int r = it * RPI_B + rb;
+      const int grow = qw0 + r;
+      const f32x4 o0 = *reinterpret_cast<const f32x4*>(my + r * ROWB + (((2 * cb) ^ (r & 15)) << 4));
+      const f32x4 o1 = *reinterpret_cast<const f32x4*>(my + r * ROWB + (((2 * cb + 1) ^ (r & 15)) << 4));
+      bf16x8 ob;
+#pragma unroll
+      for (int k = 0; k < 4; k++) {
+        ob[k] = (__bf16)o0[k];
+        ob[4 + k] = (__bf16)o1[k];
       }
+      if (grow < p.Sq) *reinterpret_cast<bf16x8*>(reinterpret_cast<__bf16*>(p.out) + ob_bh + (int64_t)grow * p.o_ss) = ob;
     }
   }
 }
