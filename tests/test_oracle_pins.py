@@ -177,6 +177,12 @@ def test_merge_order_invariance(causal):
                                     causal_diag=causal, q_offset=c * C, k_offset=j * C) for j in range(n)]
     o, l = oracle.merge_nary([p[0] for p in parts], [p[1] for p in parts])
     assert np.max(np.abs(o - ref_o[:, :, c * C:])) < 1e-13 and np.max(np.abs(l - ref_l[:, :, c * C:])) < 1e-13
+    # binary tree of pairwise Updates over the same partials
+    level = parts
+    while len(level) > 1:
+        nxt = [oracle.merge_pair(level[i][0], level[i][1], level[i + 1][0], level[i + 1][1]) for i in range(0, len(level) - 1, 2)]
+        level = nxt + ([level[-1]] if len(level) % 2 else [])
+    assert np.max(np.abs(level[0][0] - ref_o[:, :, c * C:])) < 1e-13 and np.max(np.abs(level[0][1] - ref_l[:, :, c * C:])) < 1e-13
 
 
 def test_gqa_equals_mha_with_repeated_kv():
