@@ -2,6 +2,7 @@
 import numpy as np
 import torch
 
+import oracle
 import workloads as wl
 
 
@@ -28,3 +29,17 @@ def max_abs(a, b):
     both_ninf = np.isneginf(a) & np.isneginf(b)
     d = np.abs(np.where(both_ninf, 0.0, a) - np.where(both_ninf, 0.0, b))
     return float(np.max(d)) if d.size else 0.0
+
+
+def check_rows(cfg, out, lse, qb, kb, vb, n_random, heads=None):
+    """Compare sampled rows of every head against exact oracle rows."""
+    rows = wl.sample_rows(cfg.S, cfg.chunk, n_random, seed=cfg.seed + 1)
+    G = cfg.Hq // cfg.Hkv
+    worst_o = worst_l = 0.0
+    ridx = torch.from_numpy(rows).to("cuda")
+    for h in (range(cfg.Hq) if heads is None else heads):
+        g = h // G
+        ref_o, ref_l = oracle.attention_rows(f64(qb[0, h][rows]), rows, f64(kb[0, g]), f64(vb[0, g]), cfg.scale, cfg.causal)
+        worst_o = max(worst_o, max_abs(to_np(out[0, h][ridx]), ref_o))
+        worst_l = max(worst_l, max_abs(to_np(lse[0, h][ridx]), ref_l))
+    return worst_o, worst_l, len(rows)

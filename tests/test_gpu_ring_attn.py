@@ -11,7 +11,7 @@ import torch
 
 import oracle
 import workloads as wl
-from gpu_util import bits_to_dev, f64, max_abs, rand_bits, to_np
+from gpu_util import bits_to_dev, check_rows as _check_rows, f64, max_abs, rand_bits, to_np
 
 pytestmark = pytest.mark.gpu
 OUT_TOL, LSE_TOL = 1e-2, 1e-3
@@ -96,20 +96,6 @@ def test_ring_is_bitwise_reproducible(lib):
     a = _ring(lib, q, k, v, 4, True)
     b = _ring(lib, q, k, v, 4, True, poison=False)
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
-
-
-def _check_rows(cfg, out, lse, qb, kb, vb, n_random, heads=None):
-    """Compare sampled rows of every head against exact oracle rows."""
-    rows = wl.sample_rows(cfg.S, cfg.chunk, n_random, seed=cfg.seed + 1)
-    G = cfg.Hq // cfg.Hkv
-    worst_o = worst_l = 0.0
-    ridx = torch.from_numpy(rows).to("cuda")
-    for h in (range(cfg.Hq) if heads is None else heads):
-        g = h // G
-        ref_o, ref_l = oracle.attention_rows(f64(qb[0, h][rows]), rows, f64(kb[0, g]), f64(vb[0, g]), cfg.scale, cfg.causal)
-        worst_o = max(worst_o, max_abs(to_np(out[0, h][ridx]), ref_o))
-        worst_l = max(worst_l, max_abs(to_np(lse[0, h][ridx]), ref_l))
-    return worst_o, worst_l, len(rows)
 
 
 def test_ring_config3_causal_32k_8_chunks_sampled_rows(lib):

@@ -8,8 +8,7 @@ import torch
 
 import oracle
 import workloads as wl
-from gpu_util import bits_to_dev, f64, max_abs, rand_bits, to_np
-from test_gpu_ring_attn import _check_rows
+from gpu_util import bits_to_dev, check_rows as _check_rows, f64, max_abs, rand_bits, to_np
 
 pytestmark = pytest.mark.gpu
 OUT_TOL, LSE_TOL = 1e-2, 1e-3
