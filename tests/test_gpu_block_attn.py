@@ -8,6 +8,7 @@ import pytest
 import torch
 
 import oracle
+import workloads as wl
 from gpu_util import bits_to_dev, f64, max_abs, rand_bits, to_np
 
 pytestmark = pytest.mark.gpu
@@ -129,3 +130,73 @@ def test_block_attn_is_deterministic(lib):
     a = _run_block(lib, qb, kb, vb, 0.088, lib.TR_MASK_CAUSAL_DIAG, torch.float32)
     b = _run_block(lib, qb, kb, vb, 0.088, lib.TR_MASK_CAUSAL_DIAG, torch.float32)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        D = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2, 3]))
+        G = int(rng.choice([1, 2, 4]))
+        # key counts around every tile-count boundary of the 4-deep 64-key ring (1 .. 10 tiles) and ragged tails
+        Sk = int(rng.choice([int(rng.integers(1, 70)), 64 * int(rng.integers(1, 10)) + int(rng.integers(-2, 3)), int(rng.integers(1, 700))]))
+        Sq = int(rng.choice([int(rng.integers(1, 40)), 256 * int(rng.integers(1, 3)) + int(rng.integers(-3, 4)), int(rng.integers(1, 600))]))
+        kind = int(rng.integers(0, 3))          # 0 none, 1 causal at random positions, 2 fused Update (no mask)
+        q_pos0, k_pos0 = (int(rng.integers(0, 400)), int(rng.integers(0, 400))) if kind == 1 else (0, 0)
+        cases.append((i, D, Hkv, G, max(Sq, 1), max(Sk, 1), kind, q_pos0, k_pos0))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(36, 20260), ids=lambda c: f"{c[0]}-D{c[1]}-Hkv{c[2]}x{c[3]}-Sq{c[4]}-Sk{c[5]}-k{c[6]}")
+def test_block_attn_seeded_random_shapes(lib, case):
+    """Seeded sweep over shapes that straddle wave, tile and ring-depth boundaries, with GQA, causal offsets
+    and the fused Update epilogue; every element is compared with the oracle."""
+    i, D, Hkv, G, Sq, Sk, kind, q_pos0, k_pos0 = case
+    B, Hq, scale = 1, Hkv * G, 1.0 / np.sqrt(D)
+    qb, kb, vb = rand_bits((B, Hq, Sq, D), 500 + 3 * i), rand_bits((B, Hkv, Sk, D), 501 + 3 * i), rand_bits((B, Hkv, Sk, D), 502 + 3 * i)
+    if kind == 2:
+        rng = np.random.default_rng(900 + i)
+        acc_o = rng.standard_normal((B, Hq, Sq, D)).astype(np.float32)
+        acc_l = rng.uniform(-5, 15, (B, Hq, Sq)).astype(np.float32)
+        acc_l[:, :, ::7] = -np.inf                                   # some empty accumulator rows
+        o = torch.from_numpy(acc_o).to("cuda"); l = torch.from_numpy(acc_l).to("cuda")
+        lib.tr_block_attn_merge(bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb), lib.TR_MASK_NONE, scale, o, l)
+        torch.cuda.synchronize()
+        blk_o, blk_l = oracle.attention_block(f64(qb), f64(kb), f64(vb), scale)
+        clean = np.where(np.isneginf(acc_l)[..., None], 0.0, acc_o)
+        ref_o, ref_l = oracle.merge_pair(clean, acc_l, blk_o, blk_l)
+        out, lse = to_np(o), to_np(l)
+    elif kind == 1:
+        out, lse = _run_block(lib, qb, kb, vb, scale, None, torch.float32, causal_at=(q_pos0, k_pos0))
+        ref_o, ref_l = oracle.attention_block(f64(qb), f64(kb), f64(vb), scale, causal_diag=True, q_offset=q_pos0, k_offset=k_pos0)
+    else:
+        out, lse = _run_block(lib, qb, kb, vb, scale, lib.TR_MASK_NONE, torch.float32)
+        ref_o, ref_l = oracle.attention_block(f64(qb), f64(kb), f64(vb), scale)
+    assert not np.isnan(out).any() and not np.isnan(lse).any()
+    assert max_abs(out, ref_o) <= OUT_TOL and max_abs(lse, ref_l) <= LSE_TOL
+
+
+@pytest.mark.parametrize("profile", ["rising", "falling", "late_spike", "early_spike", "plateaus"])
+def test_block_attn_adversarial_score_profiles(lib, profile):
+    """Score profiles along the keys that stress the exponent reference of the softmax: a reference taken early
+    must be raised again and again (rising), must not be lost to underflow (falling), and a single late or
+    early outlier must take over / keep the row."""
+    B, H, Sq, Sk, D = 1, 2, 96, 330, 128
+    rng = np.random.default_rng(77)
+    q = np.zeros((B, H, Sq, D), dtype=np.float32)
+    k = (rng.standard_normal((B, H, Sk, D)) * 0.05).astype(np.float32)
+    v = rng.standard_normal((B, H, Sk, D)).astype(np.float32)
+    q[..., 0] = 1.0 + (np.arange(Sq) % 5)[None, None, :] * 0.25            # rows differ a little
+    q[..., 1:] = (rng.standard_normal((B, H, Sq, D - 1)) * 0.05).astype(np.float32)
+    c = np.arange(Sk, dtype=np.float32)
+    ramp = {"rising": 0.5 * c, "falling": -0.5 * c,
+            "late_spike": np.where(c == Sk - 7, 220.0, 0.0), "early_spike": np.where(c == 3, 220.0, 0.0),
+            "plateaus": 40.0 * np.floor(c / 50.0)}[profile].astype(np.float32)
+    k[..., 0] = ramp[None, None, :]
+    qb, kb, vb = (wl.f32_to_bf16_bits(x) for x in (q, k, v))
+    out, lse = _run_block(lib, qb, kb, vb, 1.0, lib.TR_MASK_NONE, torch.float32)
+    ref_o, ref_l = oracle.attention_block(f64(qb), f64(kb), f64(vb), 1.0)
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    assert max_abs(out, ref_o) <= OUT_TOL
+    assert max_abs(lse, ref_l) <= LSE_TOL + 2e-6 * np.abs(ref_l).max()      # fp32 lse of magnitude up to a few hundred
