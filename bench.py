@@ -220,7 +220,7 @@ def bench_merge_only(tr, wl, steps, warmup):
     return res
 
 
-def bench_ring(tr, wl, name, steps, warmup, fused, schedule=None, n_inner=1):
+def bench_ring(tr, wl, name, steps, warmup, fused, schedule=None, n_inner=1, block_dtype=None):
     """tr_ring_attn over a whole sequence; fused: Update in the attention epilogue (no workspace), else two kernels.
     schedule: None = tr_ring_attn (Algorithm 1), else a TR_SCHED_* value run through tr_ring_attn_sched."""
     import torch
@@ -233,7 +233,9 @@ def bench_ring(tr, wl, name, steps, warmup, fused, schedule=None, n_inner=1):
     ws = None if fused else torch.empty(tr.tr_ring_attn_workspace_bytes(q, cfg.n_chunks), dtype=torch.uint8, device="cuda")
 
     def run():
-        if schedule is None:
+        if block_dtype is not None:     # two-kernel form with a chosen transport format of block_out
+            tr.tr_ring_attn_blocks(q, k, v, cfg.n_chunks, cfg.causal, out, lse, block_dtype, ws, cfg.scale)
+        elif schedule is None:
             tr.tr_ring_attn(q, k, v, cfg.n_chunks, cfg.causal, out, lse, cfg.scale, ws)
         else:
             tr.tr_ring_attn_sched(q, k, v, cfg.n_chunks, cfg.causal, schedule, out, lse, cfg.scale, n_inner)
@@ -255,7 +257,8 @@ def bench_ring(tr, wl, name, steps, warmup, fused, schedule=None, n_inner=1):
     sched_name = {None: "Algorithm 1", 0: "Algorithm 1", 1: "Ring Attention order", 2: "zigzag partition",
                   3: f"hybrid, {n_inner} devices per node"}[schedule]
     return {"workload": f"{name}: S={cfg.S} as {n} segments, Hq={cfg.Hq}, Hkv={cfg.Hkv}, causal={cfg.causal}, {sched_name}",
-            "form": "Update fused into the attention epilogue" if fused else "tr_block_attn + tr_merge per step",
+            "form": ("Update fused into the attention epilogue" if fused else
+                     "tr_block_attn + tr_merge per step" + (", bf16 block_out" if block_dtype == tr.TR_BF16 else ", fp32 block_out")),
             "block_steps": full_steps + diag_steps, "ms": ms, "tflops": flops / (ms * 1e-3) / 1e12,
             "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
 
@@ -345,6 +348,7 @@ def main():
             "ring_cfg1": bench_ring_small(tr, wl),
             "ring_cfg3": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True),
             "ring_cfg3_two_kernel": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=False),
+            "ring_cfg3_two_kernel_bf16_blocks": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=False, block_dtype=tr.TR_BF16),
             "ring_cfg3_zigzag": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True, schedule=tr.TR_SCHED_ZIGZAG),
             "ring_cfg3_hybrid_2x4": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True, schedule=tr.TR_SCHED_HYBRID, n_inner=4),
             "ring_cfg5": bench_ring(tr, wl, "cfg5_gqa", 2, 1, fused=True),

@@ -156,6 +156,21 @@ tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* 
                        const tr_tensor* out, const tr_tensor* lse, float scale,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Algorithm 1 in its literal two-kernel form with a chosen format for the block result that
+ * travels between the Attention and the Update (Sec. 3.1 notes the volume of block_out and
+ * block_lse): block_dtype = TR_F32 is tr_ring_attn with a workspace; TR_BF16 halves block_out
+ * (what a multi-device run would put on the wire) at the cost of one bf16 rounding (2^-9
+ * relative) of every block before it is merged.  block_lse stays fp32.  The workspace is
+ * required, 256-byte aligned, at least tr_ring_attn_blocks_workspace_bytes(q, n_chunks,
+ * block_dtype) bytes.  Everything else as in tr_ring_attn.
+ */
+tr_status tr_ring_attn_blocks(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v,
+                              int n_chunks, int causal,
+                              const tr_tensor* out, const tr_tensor* lse, float scale,
+                              int block_dtype, void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t tr_ring_attn_blocks_workspace_bytes(const tr_tensor* q, int n_chunks, int block_dtype);
+
 /* Order in which tr_ring_attn_sched runs the block steps (all "devices" replayed on one GPU). */
 typedef enum {
   TR_SCHED_TOKENRING = 0,      /* Algorithm 1: Q circulates, device j keeps K_j, V_j              */

@@ -67,6 +67,11 @@ def _load():
     lib.tr_ring_attn_sched.argtypes = [P, P, P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P, ctypes.c_float,
                                        ctypes.c_void_p]
     lib.tr_ring_attn_sched.restype = ctypes.c_int
+    lib.tr_ring_attn_blocks.argtypes = [P, P, P, ctypes.c_int, ctypes.c_int, P, P, ctypes.c_float, ctypes.c_int,
+                                        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.tr_ring_attn_blocks.restype = ctypes.c_int
+    lib.tr_ring_attn_blocks_workspace_bytes.argtypes = [P, ctypes.c_int, ctypes.c_int]
+    lib.tr_ring_attn_blocks_workspace_bytes.restype = ctypes.c_size_t
     lib.tr_ring_attn_workspace_bytes.argtypes = [P, ctypes.c_int]
     lib.tr_ring_attn_workspace_bytes.restype = ctypes.c_size_t
     lib.tr_last_error.argtypes = []
@@ -183,6 +188,17 @@ def tr_ring_attn_sched(q, k, v, n_devices, causal, schedule, out, lse, scale=0.0
     """tr_ring_attn with a selectable step order (TR_SCHED_*); Update fused into the attention epilogue."""
     _check(_lib.tr_ring_attn_sched(desc(q), desc(k), desc(v), int(n_devices), int(bool(causal)), int(schedule), int(n_inner),
                                    desc(out), desc(lse), float(scale), _stream(stream)))
+
+
+def tr_ring_attn_blocks_workspace_bytes(q, n_chunks, block_dtype) -> int:
+    return int(_lib.tr_ring_attn_blocks_workspace_bytes(desc(q), int(n_chunks), int(block_dtype)))
+
+
+def tr_ring_attn_blocks(q, k, v, n_chunks, causal, out, lse, block_dtype, workspace, scale=0.0, stream=None):
+    """Algorithm 1 as tr_block_attn + tr_merge per step, the block result stored as block_dtype (TR_F32 / TR_BF16)."""
+    _check(_lib.tr_ring_attn_blocks(desc(q), desc(k), desc(v), int(n_chunks), int(bool(causal)), desc(out), desc(lse),
+                                    float(scale), int(block_dtype), workspace.data_ptr(),
+                                    workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def tr_ring_attn_workspace_bytes(q, n_chunks) -> int:

@@ -381,17 +381,27 @@ tr_status tr_merge_n(const tr_tensor* out, const tr_tensor* lse, const tr_tensor
   return TR_OK;
 }
 
-size_t tr_ring_attn_workspace_bytes(const tr_tensor* q, int n_chunks) {
+size_t tr_ring_attn_blocks_workspace_bytes(const tr_tensor* q, int n_chunks, int block_dtype) {
   if (!q || n_chunks < 1 || q->B < 0 || q->H < 0 || q->S < 0 || q->D < 0 || q->S % n_chunks) return 0;
+  if (block_dtype != TR_F32 && block_dtype != TR_BF16) return 0;
   const size_t C = (size_t)(q->S / n_chunks);
   const size_t rows = (size_t)q->B * (size_t)q->H * C;
-  return align_up(rows * (size_t)q->D * 4) + align_up(rows * 4);
+  return align_up(rows * (size_t)q->D * (size_t)elem_bytes(block_dtype)) + align_up(rows * 4);
 }
 
-tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int n_chunks, int causal,
-                       const tr_tensor* out, const tr_tensor* lse, float scale, void* workspace, size_t workspace_bytes,
-                       void* hip_stream) {
-  g_err[0] = 0;
+size_t tr_ring_attn_workspace_bytes(const tr_tensor* q, int n_chunks) {
+  return tr_ring_attn_blocks_workspace_bytes(q, n_chunks, TR_F32);
+}
+
+}  // extern "C"
+
+namespace {
+
+// Algorithm 1 on one device.  workspace == NULL: fused form.  Otherwise the two-kernel form, the
+// block result passing through the workspace as block_dtype (fp32, or bf16 as a transport format).
+tr_status ring_attn_impl(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int n_chunks, int causal,
+                         const tr_tensor* out, const tr_tensor* lse, float scale, int block_dtype, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
   if (!q || !k || !v || !out || !lse) return fail(TR_ERR_NULL, "a tensor descriptor is NULL");
   if (n_chunks < 1) return fail(TR_ERR_SHAPE, "n_chunks must be >= 1");
   if (q->S < 0 || q->S % n_chunks) return fail(TR_ERR_SHAPE, "sequence length %lld is not a multiple of n_chunks %d", (long long)q->S, n_chunks);
@@ -411,7 +421,7 @@ tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* 
   if (out->B != q->B || out->H != q->H || out->S != q->S || out->D != q->D || lse->B != q->B || lse->H != q->H || lse->S != q->S || lse->D != 1)
     return fail(TR_ERR_SHAPE, "out/lse shape does not match q");
 
-  const size_t need = tr_ring_attn_workspace_bytes(q, n_chunks);
+  const size_t need = tr_ring_attn_blocks_workspace_bytes(q, n_chunks, block_dtype);
   const size_t rows = (size_t)q->B * (size_t)q->H * (size_t)C;
   tr_tensor ws_out, ws_lse;
   memset(&ws_out, 0, sizeof(ws_out));
@@ -420,13 +430,15 @@ tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* 
   if (!fused && n_chunks > 1 && rows > 0) {
     if (((uintptr_t)workspace) % kWsAlign) return fail(TR_ERR_WORKSPACE, "workspace must be %zu-byte aligned", kWsAlign);
     if (workspace_bytes < need) return fail(TR_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, need);
-    ws_out.ptr = workspace; ws_out.dtype = TR_F32;
+    ws_out.ptr = workspace; ws_out.dtype = block_dtype;
     ws_out.B = q->B; ws_out.H = q->H; ws_out.S = C; ws_out.D = q->D;
     ws_out.stride_s = q->D; ws_out.stride_h = C * q->D; ws_out.stride_b = q->H * C * q->D;
     ws_lse = ws_out;
-    ws_lse.ptr = (char*)workspace + align_up(rows * (size_t)q->D * 4);
+    ws_lse.ptr = (char*)workspace + align_up(rows * (size_t)q->D * (size_t)elem_bytes(block_dtype));
+    ws_lse.dtype = TR_F32;
     ws_lse.D = 1; ws_lse.stride_s = 1; ws_lse.stride_h = C; ws_lse.stride_b = q->H * C;
     tr_tensor ws_all = ws_out;  // alias check of the whole workspace against the user tensors
+    ws_all.dtype = TR_F32;
     ws_all.B = 1; ws_all.H = 1; ws_all.S = 1; ws_all.D = (int64_t)(need / 4);
     if (overlaps(&ws_all, q) || overlaps(&ws_all, k) || overlaps(&ws_all, v) || overlaps(&ws_all, out) || overlaps(&ws_all, lse))
       return fail(TR_ERR_ALIAS, "workspace overlaps a tensor argument");
@@ -462,6 +474,26 @@ tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* 
     }
   }
   return TR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int n_chunks, int causal,
+                       const tr_tensor* out, const tr_tensor* lse, float scale, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+  g_err[0] = 0;
+  return ring_attn_impl(q, k, v, n_chunks, causal, out, lse, scale, TR_F32, workspace, workspace_bytes, hip_stream);
+}
+
+tr_status tr_ring_attn_blocks(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int n_chunks, int causal,
+                              const tr_tensor* out, const tr_tensor* lse, float scale, int block_dtype, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  g_err[0] = 0;
+  if (block_dtype != TR_F32 && block_dtype != TR_BF16) return fail(TR_ERR_DTYPE, "block_dtype %d is neither fp32 nor bf16", block_dtype);
+  if (!workspace) return fail(TR_ERR_WORKSPACE, "the two-kernel form needs a workspace");
+  return ring_attn_impl(q, k, v, n_chunks, causal, out, lse, scale, block_dtype, workspace, workspace_bytes, hip_stream);
 }
 
 tr_status tr_ring_attn_sched(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int n_devices, int causal,

@@ -133,3 +133,49 @@ def test_ring_config5_gqa_128k_16_chunks_sampled_rows(lib):
     worst_o, worst_l, n = _check_rows(cfg, out, lse, qb, kb, vb, n_random=96)
     print(f"cfg5: {n} rows x {cfg.Hq} heads, max|d out| {worst_o:.3e}, max|d lse| {worst_l:.3e}")
     assert worst_o <= OUT_TOL and worst_l <= LSE_TOL
+
+
+def test_ring_blocks_fp32_is_the_two_kernel_form_bitwise(lib):
+    qb, kb, vb = rand_bits((1, 4, 768, 128), 50), rand_bits((1, 2, 768, 128), 51), rand_bits((1, 2, 768, 128), 52)
+    q, k, v = bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb)
+    a = _ring(lib, q, k, v, 3, True, fused=False)
+    out = torch.full_like(a[0], float("nan")); lse = torch.full_like(a[1], float("nan"))
+    ws = torch.empty(lib.tr_ring_attn_blocks_workspace_bytes(q, 3, lib.TR_F32), dtype=torch.uint8, device="cuda")
+    assert ws.numel() == lib.tr_ring_attn_workspace_bytes(q, 3)
+    lib.tr_ring_attn_blocks(q, k, v, 3, True, out, lse, lib.TR_F32, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, a[0]) and torch.equal(lse, a[1])
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_ring_blocks_bf16_transport(lib, causal):
+    """block_out stored as bf16 between Attention and Update: every merged block carries one bf16 rounding,
+    i.e. at most 2^-9 of the largest block value on top of the kernel's own 1e-2; lse is untouched by it."""
+    B, Hq, Hkv, S, D, n = 1, 4, 2, 1024, 128, 4
+    qb, kb, vb = rand_bits((B, Hq, S, D), 53), rand_bits((B, Hkv, S, D), 54), rand_bits((B, Hkv, S, D), 55)
+    q, k, v = bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb)
+    out = torch.full((B, Hq, S, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((B, Hq, S), float("nan"), dtype=torch.float32, device="cuda")
+    nbytes = lib.tr_ring_attn_blocks_workspace_bytes(q, n, lib.TR_BF16)
+    assert nbytes == Hq * (S // n) * D * 2 + Hq * (S // n) * 4
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    lib.tr_ring_attn_blocks(q, k, v, n, causal, out, lse, lib.TR_BF16, ws)
+    torch.cuda.synchronize()
+    ref_o, ref_l = oracle.attention_full(f64(qb), f64(kb), f64(vb), 1.0 / np.sqrt(D), causal)
+    vmax = float(np.abs(f64(vb)).max())
+    d_o, d_l = max_abs(to_np(out), ref_o), max_abs(to_np(lse), ref_l)
+    print(f"bf16 transport, causal={causal}: max|d out| {d_o:.3e} (bound {OUT_TOL + vmax * 2.0 ** -9:.3e}), max|d lse| {d_l:.3e}")
+    assert d_o <= OUT_TOL + vmax * 2.0 ** -9 and d_l <= LSE_TOL
+    # and the same order of Updates with the oracle's blocks rounded to bf16 on the way (first block of a chunk is not)
+    C = S // n
+    o_ref = np.zeros((B, Hq, S, D)); l_ref = np.full((B, Hq, S), -np.inf)
+    seen = set()
+    for _, j, c in oracle.ring_schedule(n, causal):
+        qs, ks = slice(c * C, (c + 1) * C), slice(j * C, (j + 1) * C)
+        bo, bl = oracle.attention_block(f64(qb)[:, :, qs], f64(kb)[:, :, ks], f64(vb)[:, :, ks], 1.0 / np.sqrt(D),
+                                        causal_diag=causal, q_offset=c * C, k_offset=j * C)
+        if c in seen:
+            bo = wl.bf16_bits_to_f64(wl.f32_to_bf16_bits(bo.astype(np.float32)))
+        seen.add(c)
+        o_ref[:, :, qs], l_ref[:, :, qs] = oracle.merge_pair(o_ref[:, :, qs], l_ref[:, :, qs], bo, bl)
+    assert max_abs(to_np(out), o_ref) <= OUT_TOL + vmax * 2.0 ** -8 and max_abs(to_np(lse), l_ref) <= LSE_TOL
