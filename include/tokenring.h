@@ -220,11 +220,14 @@ tr_status tr_time_next_kernel(void* start_event, void* stop_event);
  * 16 fragments of 64 lanes x 8 bf16, first the 8 A then the 8 B fragments, 16-byte aligned;
  * the values are the caller's choice, e.g. the distribution of the real workload).  Timed
  * with tr_time_next_kernel it gives the MFMA rate the chip sustains for that data, the
- * practical ceiling next to which an MFMA-bound kernel can be read.  `sink` (device, >= 4
- * bytes) is only there to keep the results live.  *flop_out (host, may be NULL) receives the
- * flop count of the launch.  Enqueues on hip_stream and returns without synchronising.
+ * practical ceiling next to which an MFMA-bound kernel can be read.  idle in {0, 1, 2, 4, 8}:
+ * every wave additionally sleeps 64 * idle cycles after each 8 MFMAs, which lowers the duty
+ * cycle of the MFMA pipe with no other work added (how the sustained clock responds to the
+ * duty cycle alone).  `sink` (device, >= 4 bytes) is only there to keep the results live.
+ * *flop_out (host, may be NULL) receives the flop count of the launch.  Enqueues on hip_stream
+ * and returns without synchronising.
  */
-tr_status tr_probe_mfma(const void* operands, size_t operand_bytes, void* sink, int iters, int n_blocks,
+tr_status tr_probe_mfma(const void* operands, size_t operand_bytes, void* sink, int iters, int idle, int n_blocks,
                         double* flop_out, void* hip_stream);
 
 /* Description of the last error on the calling thread ("" if none). Static storage. */

@@ -247,7 +247,7 @@ tr_status tr_time_next_kernel(void* start_event, void* stop_event) {
   g_timing.stop = static_cast<hipEvent_t>(stop_event);
   return TR_OK;
 }
-tr_status tr_probe_mfma(const void* operands, size_t operand_bytes, void* sink, int iters, int n_blocks,
+tr_status tr_probe_mfma(const void* operands, size_t operand_bytes, void* sink, int iters, int idle, int n_blocks,
                         double* flop_out, void* hip_stream) {
   g_err[0] = 0;
   if (!operands || !sink) return fail(TR_ERR_NULL, "tr_probe_mfma: operands and sink must not be NULL");
@@ -256,7 +256,8 @@ tr_status tr_probe_mfma(const void* operands, size_t operand_bytes, void* sink, 
   if (((uintptr_t)operands & 15) != 0) return fail(TR_ERR_STRIDE, "tr_probe_mfma: operands must be 16-byte aligned");
   if (iters < 1 || iters > (1 << 24) || n_blocks < 1 || n_blocks > (1 << 20))
     return fail(TR_ERR_SHAPE, "tr_probe_mfma: iters %d / n_blocks %d out of range", iters, n_blocks);
-  const hipError_t e = tr::launch_mfma_probe(operands, static_cast<float*>(sink), iters, n_blocks, static_cast<hipStream_t>(hip_stream));
+  if (idle != 0 && idle != 1 && idle != 2 && idle != 4 && idle != 8) return fail(TR_ERR_UNSUPPORTED, "tr_probe_mfma: idle must be 0, 1, 2, 4 or 8 (got %d)", idle);
+  const hipError_t e = tr::launch_mfma_probe(operands, static_cast<float*>(sink), iters, idle, n_blocks, static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(TR_ERR_HIP, "tr_probe_mfma: launch failed: %s", hipGetErrorString(e));
   // waves per block * MFMAs per wave * flop per 32x32x16 MFMA
   if (flop_out) *flop_out = (double)n_blocks * (tr::mfma_probe_threads() / 64) * 8.0 * iters * 32768.0;

@@ -13,6 +13,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kProbeThreads = 512;  // 8 waves per CU, two per SIMD, like the attention kernel
 constexpr int kProbeOps = 8;        // operand pairs rotated through
 
+// IDLE > 0 puts every wave to sleep for 64 * IDLE cycles after each 8 MFMAs, which lowers the
+// duty cycle of the MFMA pipe without adding any other work.
+template <int IDLE>
 __global__ void __launch_bounds__(kProbeThreads) mfma_probe_kernel(const bf16x8* ops, float* sink, int iters) {
   const int lane = threadIdx.x & 63;
   bf16x8 a[kProbeOps], b[kProbeOps];
@@ -30,6 +33,7 @@ __global__ void __launch_bounds__(kProbeThreads) mfma_probe_kernel(const bf16x8*
       c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i + 2], b[i + 1], c2, 0, 0, 0);
       c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i + 3], b[i], c3, 0, 0, 0);
     }
+    if (IDLE > 0) __builtin_amdgcn_s_sleep(IDLE);
   }
   float s = 0.f;
 #pragma unroll
@@ -39,9 +43,17 @@ __global__ void __launch_bounds__(kProbeThreads) mfma_probe_kernel(const bf16x8*
 
 }  // namespace
 
-hipError_t launch_mfma_probe(const void* operands, float* sink, int iters, int n_blocks, hipStream_t stream) {
-  return launch_kernel(mfma_probe_kernel, dim3((unsigned)n_blocks), dim3(kProbeThreads), 0, stream,
-                       static_cast<const bf16x8*>(operands), sink, iters);
+hipError_t launch_mfma_probe(const void* operands, float* sink, int iters, int idle, int n_blocks, hipStream_t stream) {
+  const dim3 grid((unsigned)n_blocks), block(kProbeThreads);
+  const bf16x8* ops = static_cast<const bf16x8*>(operands);
+  switch (idle) {
+    case 0: return launch_kernel(mfma_probe_kernel<0>, grid, block, 0, stream, ops, sink, iters);
+    case 1: return launch_kernel(mfma_probe_kernel<1>, grid, block, 0, stream, ops, sink, iters);
+    case 2: return launch_kernel(mfma_probe_kernel<2>, grid, block, 0, stream, ops, sink, iters);
+    case 4: return launch_kernel(mfma_probe_kernel<4>, grid, block, 0, stream, ops, sink, iters);
+    case 8: return launch_kernel(mfma_probe_kernel<8>, grid, block, 0, stream, ops, sink, iters);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 int mfma_probe_threads() { return kProbeThreads; }

@@ -141,11 +141,12 @@ def test_merge_n_and_sched_reject_bad_arguments(tr):
 def test_probe_rejects_bad_arguments(tr):
     lib = tr.raw_lib()
     ok_ptr, sink = 0x7F0000000000, 0x7F0000100000
-    assert lib.tr_probe_mfma(None, 16384, sink, 10, 4, None, None) == 1
-    assert lib.tr_probe_mfma(ok_ptr, 16383, sink, 10, 4, None, None) == 3
-    assert lib.tr_probe_mfma(ok_ptr + 2, 16384, sink, 10, 4, None, None) == 4
-    assert lib.tr_probe_mfma(ok_ptr, 16384, sink, 0, 4, None, None) == 3
-    assert lib.tr_probe_mfma(ok_ptr, 16384, sink, 10, 0, None, None) == 3
+    assert lib.tr_probe_mfma(None, 16384, sink, 10, 0, 4, None, None) == 1
+    assert lib.tr_probe_mfma(ok_ptr, 16383, sink, 10, 0, 4, None, None) == 3
+    assert lib.tr_probe_mfma(ok_ptr + 2, 16384, sink, 10, 0, 4, None, None) == 4
+    assert lib.tr_probe_mfma(ok_ptr, 16384, sink, 0, 0, 4, None, None) == 3
+    assert lib.tr_probe_mfma(ok_ptr, 16384, sink, 10, 0, 0, None, None) == 3
+    assert lib.tr_probe_mfma(ok_ptr, 16384, sink, 10, 3, 4, None, None) == 6
     assert b"tr_probe_mfma" in lib.tr_last_error()
 
 
