@@ -70,7 +70,8 @@ typedef struct {
  *   q   [B,Hq,Sq,D] bf16      k, v [B,Hkv,Sk,D] bf16      D in {64, 128}
  *   out [B,Hq,Sq,D] bf16 or fp32 (written)                lse [B,Hq,Sq] fp32 (written)
  * Sq and Sk are arbitrary (0 allowed; Sk == 0 gives out = 0, lse = -inf).
- * Strides of q/k/v/out must be multiples of 8 elements (16-byte rows).
+ * Strides of q/k/v/out must be multiples of 8 elements (16-byte rows); stride_s of k and v at
+ * most 2^24 elements.
  * Arithmetic: bf16 MFMA with fp32 accumulation, fp32 softmax, probabilities rounded to
  * bf16 before the PV product.
  */

@@ -96,6 +96,9 @@ tr_status attn_common(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v
   if (overlaps(out, q) || overlaps(out, k) || overlaps(out, v) || overlaps(lse, q) || overlaps(lse, k) || overlaps(lse, v) || overlaps(out, lse))
     return fail(TR_ERR_ALIAS, "outputs overlap inputs or each other");
   if ((int64_t)q->B * q->H > (1 << 24)) return fail(TR_ERR_SHAPE, "too many (batch, head) pairs");
+  // the K/V staging addresses a 64-key tile with 32-bit byte offsets from the tile base
+  if (k->stride_s > ((int64_t)1 << 24) || v->stride_s > ((int64_t)1 << 24))
+    return fail(TR_ERR_STRIDE, "stride_s of k and v must not exceed 2^24 elements");
 
   tr::AttnParams p;
   memset(&p, 0, sizeof(p));

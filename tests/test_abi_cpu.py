@@ -65,6 +65,9 @@ def test_block_attn_rejects_bad_arguments(tr):
     assert call(q=_t(tr, tr.TR_BF16, 1, 4, 128, 128, strides=(4 * 128 * 128, 128 * 128, 100)))[0] == 4   # stride_s < D
     assert call(q=_t(tr, tr.TR_BF16, 1, 4, 128, 128, strides=(4 * 128 * 132, 128 * 132, 132)))[0] == 4   # rows not 16-byte multiples
     assert call(q=_t(tr, tr.TR_BF16, 1, 4, 128, 128, ptr=0x7F0000000002))[0] == 4           # misaligned pointer
+    big = (1 << 24) + 8                                                                     # K/V row stride beyond the staging offsets
+    st, msg = call(k=_t(tr, tr.TR_BF16, 1, 2, 128, 128, ptr=0x7F1000000000, strides=(2 * 128 * big, 128 * big, big)))
+    assert st == 4 and "2^24" in msg
     assert call(o=_t(tr, tr.TR_F32, 1, 4, 128, 128, ptr=0x7F0000000000))[0] == 5            # out aliases q
     assert lib.tr_block_attn_causal_at(B(q), B(k), B(v), -1, 0, 0.1, B(o), B(l), None) == 3
     # the fused form merges into fp32 accumulators only
