@@ -179,3 +179,20 @@ def test_ring_blocks_bf16_transport(lib, causal):
         seen.add(c)
         o_ref[:, :, qs], l_ref[:, :, qs] = oracle.merge_pair(o_ref[:, :, qs], l_ref[:, :, qs], bo, bl)
     assert max_abs(to_np(out), o_ref) <= OUT_TOL + vmax * 2.0 ** -8 and max_abs(to_np(lse), l_ref) <= LSE_TOL
+
+
+def test_ring_config3_bf16_transport_sampled_rows(lib):
+    """cfg3 in the two-kernel form with bf16 block_out between Attention and Update (one bf16 rounding per merged block)."""
+    cfg = wl.CONFIGS["cfg3_ring"]
+    qb, kb, vb = wl.make_qkv_bits(cfg)
+    q, k, v = bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb)
+    out = torch.full((cfg.B, cfg.Hq, cfg.S, cfg.D), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((cfg.B, cfg.Hq, cfg.S), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(lib.tr_ring_attn_blocks_workspace_bytes(q, cfg.n_chunks, lib.TR_BF16), dtype=torch.uint8, device="cuda")
+    lib.tr_ring_attn_blocks(q, k, v, cfg.n_chunks, True, out, lse, lib.TR_BF16, ws, cfg.scale)
+    torch.cuda.synchronize()
+    assert not torch.isnan(out).any() and not torch.isnan(lse).any()
+    worst_o, worst_l, n = _check_rows(cfg, out, lse, qb, kb, vb, n_random=128)
+    vmax = float(np.abs(f64(vb)).max())
+    print(f"cfg3 bf16 transport: {n} rows x {cfg.Hq} heads, max|d out| {worst_o:.3e} (bound {OUT_TOL + vmax * 2.0 ** -9:.3e}), max|d lse| {worst_l:.3e}")
+    assert worst_o <= OUT_TOL + vmax * 2.0 ** -9 and worst_l <= LSE_TOL

@@ -68,12 +68,12 @@ def test_schedule_argument_errors(lib):
         lib.tr_ring_attn_sched(q, q, q, 4, True, 9, out, lse)
 
 
-@pytest.mark.parametrize("name,n_inner", [("zigzag", 1), ("hybrid", 4)])
+@pytest.mark.parametrize("name,n_inner", [("zigzag", 1), ("hybrid", 4), ("ring", 1)])
 def test_config3_shape_other_schedules_sampled_rows(lib, name, n_inner):
-    """cfg3 (causal, S = 32768, 8 devices): zigzag over 16 segments of 2048, and 2 nodes x 4 devices."""
+    """cfg3 (causal, S = 32768, 8 devices): zigzag over 16 segments of 2048, 2 nodes x 4 devices, Ring Attention order."""
     cfg = wl.CONFIGS["cfg3_ring"]
     qb, kb, vb = wl.make_qkv_bits(cfg)
-    schedule = lib.TR_SCHED_ZIGZAG if name == "zigzag" else lib.TR_SCHED_HYBRID
+    schedule = {"zigzag": lib.TR_SCHED_ZIGZAG, "hybrid": lib.TR_SCHED_HYBRID, "ring": lib.TR_SCHED_RING_ATTENTION}[name]
     out, lse = _sched(lib, bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb), cfg.n_chunks, True, schedule, n_inner, cfg.scale)
     assert not torch.isnan(out).any() and not torch.isnan(lse).any()
     worst_o, worst_l, n = _check_rows(cfg, out, lse, qb, kb, vb, n_random=128)
