@@ -189,7 +189,8 @@ typedef enum {
  *   TR_SCHED_RING_ATTENTION for i, for j: Q chunk j  x  K/V chunk (j-i) mod n
  *   TR_SCHED_ZIGZAG         for i, for j: the Query pair {c, 2n-1-c}, c = (j-i) mod n, against the K/V pair
  *                           {j, 2n-1-j}; of the four segment pairs the causal rule keeps two full ones
- *                           (three on i == 0, two of them diagonal), so every (i, j) carries the same work
+ *                           (three on i == 0, two of them diagonal), so every (i, j) carries the same work; within
+ *                           an iteration the devices' pairs are issued slot by slot (all first pairs, then all second, ...)
  *   TR_SCHED_HYBRID         n_devices = nodes x n_inner; for t < nodes, for i < n_inner, for node, for p:
  *                           Q chunk node*n_inner + (p-i) mod n_inner  x  K/V chunk ((node-t) mod nodes)*n_inner + p
  *                           (n_inner is ignored by the other schedules)

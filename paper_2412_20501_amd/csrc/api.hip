@@ -175,13 +175,22 @@ int build_schedule(int schedule, int n, int n_inner, bool causal, std::vector<Ri
         for (int j = 0; j < n; j++) add(j, pmod(j - i, n));
       return n;
     case TR_SCHED_ZIGZAG:
-      for (int i = 0; i < n; i++)
-        for (int j = 0; j < n; j++) {
-          const int c = pmod(j - i, n);
-          const int qseg[2] = {c, 2 * n - 1 - c}, kseg[2] = {j, 2 * n - 1 - j};
-          for (int a = 0; a < 2; a++)
-            for (int b = 0; b < 2; b++) add(qseg[a], kseg[b]);
+      // Within an iteration the devices work concurrently, each on up to three segment pairs of
+      // its own Query pair; they are emitted slot by slot (every device's first pair, then every
+      // device's second, ...) so that pairs on distinct Query segments are adjacent and can share
+      // a launch.  The order of the blocks each Query segment receives is unaffected.
+      for (int i = 0; i < n; i++) {
+        for (int slot = 0; slot < 4; slot++) {
+          for (int j = 0; j < n; j++) {
+            const int c = pmod(j - i, n);
+            const int qseg[2] = {c, 2 * n - 1 - c}, kseg[2] = {j, 2 * n - 1 - j};
+            int kept = 0;
+            for (int a = 0; a < 2; a++)
+              for (int b = 0; b < 2; b++)
+                if (kseg[b] <= qseg[a] && kept++ == slot) steps.push_back({qseg[a], kseg[b]});
+          }
         }
+      }
       return 2 * n;
     case TR_SCHED_HYBRID: {
       const int nodes = n / n_inner;
