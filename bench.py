@@ -310,6 +310,8 @@ def main():
 
     import torch
 
+    from paper_2412_20501_amd.build import ensure_built
+    ensure_built()              # compiles only if no library has been built yet
     import paper_2412_20501_amd as tr
     import workloads as wl
     if not torch.cuda.is_available():

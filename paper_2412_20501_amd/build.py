@@ -36,5 +36,10 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def ensure_built() -> str:
+    """Build only if no library is there yet (what is already built is loaded as it is)."""
+    return LIB_PATH if os.path.exists(LIB_PATH) else build_library()
+
+
 if __name__ == "__main__":
     print(build_library(verbose="-v" in sys.argv))

@@ -14,6 +14,9 @@ def pytest_configure(config):
 
 @pytest.fixture(scope="session")
 def lib():
-    """The loaded HIP library's Python binding; GPU tests fail loudly if it is not built."""
+    """The loaded HIP library's Python binding (built first only if no library is there yet).
+    There is no fallback: if it cannot be built or loaded, every GPU test errors out."""
+    from paper_2412_20501_amd.build import ensure_built
+    ensure_built()
     import paper_2412_20501_amd as tr
     return tr
