@@ -155,6 +155,19 @@ def test_probe_rejects_bad_arguments(tr):
     assert b"tr_probe_mfma" in lib.tr_last_error()
 
 
+def test_header_and_library_work_from_plain_c(tr, tmp_path):
+    """include/tokenring.h compiles as strict C99 and a C program linked against the library gets the
+    documented status codes (validation only; nothing is launched)."""
+    import subprocess
+    src = os.path.join(ROOT, "tests", "c_abi", "abi_check.c")
+    exe = str(tmp_path / "abi_check")
+    lib_dir = os.path.dirname(tr.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), src,
+                    "-L", lib_dir, "-ltokenring", "-Wl,-rpath," + lib_dir, "-o", exe], check=True, capture_output=True, text=True)
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0 and "c abi ok" in res.stdout, res.stdout + res.stderr
+
+
 def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
     """No fallback: a missing libtokenring.so is an ImportError, not a silent CPU path."""
     import importlib
