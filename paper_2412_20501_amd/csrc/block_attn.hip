@@ -20,11 +20,11 @@
 //     MFMA : O += V_{j-1}^T P_{j-1}      and      S_{j+1} = K_{j+1} Q^T
 //     VALU : P_j = exp2((S_j - m_ref) * scale*log2e), row sums
 // with no dependency between the two halves.  Two such waves per SIMD fill each other's
-// gaps.  A workgroup has 8 waves of 32 query rows (256 rows); K/V tiles of 64 keys (two
-// sub-tiles) go straight from global memory into 4-deep LDS rings (global_load_lds), the K
-// tile with a 16-byte XOR swizzle and the V tile with a 32-byte XOR swizzle that make the
-// ds_read_b128 and the transposing reads bank-conflict free.  One workgroup barrier per
-// 64-key tile hands ring slots over.
+// gaps.  A workgroup has 8 waves of 32 query rows (256 rows); K/V tiles of 16 KiB (64 keys
+// = two sub-tiles at D = 128, 128 keys = four at D = 64) go straight from global memory into
+// 4-deep LDS rings (global_load_lds), the K tile with a 16-byte XOR swizzle and the V tile
+// with a 32-byte XOR swizzle that make the ds_read_b128 and the transposing reads
+// bank-conflict free.  One workgroup barrier per tile hands ring slots over.
 #include <type_traits>
 
 #include <atomic>
@@ -45,7 +45,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
 constexpr int kBM = kWaves * 32;  // query rows per workgroup
-constexpr int kBN = 64;           // keys per LDS tile
+// keys per LDS tile: 16 KiB of K (and of V) either way, so a tile is 2 sub-tiles of 32 keys at
+// D = 128 and 4 at D = 64, where a sub-tile carries half the MFMA work per barrier otherwise
+template <int D>
+constexpr int tile_keys() { return D == 64 ? 128 : 64; }
 constexpr int kRing = 4;          // LDS ring depth (tiles) of K and of V
 constexpr int kEpiBf16 = 0, kEpiF32 = 1, kEpiMerge = 2;
 
@@ -136,11 +139,14 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   constexpr int KS = D / 16;               // MFMA k-steps over the head dim
   constexpr int DB = D / 32;               // 32-wide d blocks of the output
   constexpr int CPR = D / 8;               // 16-byte chunks per row
-  constexpr int TILE_BYTES = kBN * RB;
+  constexpr int BN = tile_keys<D>();       // keys per LDS tile
+  constexpr int TILE_BYTES = BN * RB;
   constexpr int RPI = 1024 / RB;           // tile rows one wave-wide 16-byte load instruction covers
-  constexpr int IPW = kBN / RPI / kWaves;  // load instructions per wave, tile and tensor
+  constexpr int IPW = BN / RPI / kWaves;   // load instructions per wave, tile and tensor
   constexpr int NS = kRing;                // ring depth of the K and of the V tiles
   constexpr int SUB = 32;                  // keys per sub-tile (one MFMA row block)
+  constexpr int NSUB = BN / SUB;           // sub-tiles (= steps) per tile
+  static_assert(NSUB % 2 == 0, "the S / P register sets alternate with the step parity");
   static_assert(IPW >= 1, "tile too small for the workgroup");
 
   extern __shared__ __attribute__((aligned(1024))) char lds[];  // K ring | V ring
@@ -174,7 +180,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   const int q_last_wg = min(q0 + kBM, p.Sq) - 1;
   int kv_end = p.Sk;
   if (causal) kv_end = max(0, min(p.Sk, q_last_wg + p.causal_off + 1));
-  const int n_tiles = (kv_end + kBN - 1) / kBN;
+  const int n_tiles = (kv_end + BN - 1) / BN;
   int wave_kv_end = 0;
   if (qw0 < p.Sq) {
     wave_kv_end = p.Sk;
@@ -182,8 +188,8 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   }
   const int jw = (wave_kv_end + SUB - 1) / SUB;  // sub-tiles this wave has visible keys in
   // wave-uniform loop bounds, forced into scalar registers so that every per-step test is one compare
-  const int jw_even = __builtin_amdgcn_readfirstlane(jw);                          // last even step index allowed
-  const int jw_odd = __builtin_amdgcn_readfirstlane(min(jw, 2 * n_tiles - 1));     // last odd step index allowed
+  const int jw_first = __builtin_amdgcn_readfirstlane(jw);                            // last allowed step that opens a tile
+  const int jw_in = __builtin_amdgcn_readfirstlane(min(jw, NSUB * n_tiles - 1));      // last allowed step inside a tile
   // a sub-tile starting at kstart needs masking iff kstart > kmask_from
   int kmask_from_v = p.Sk - SUB;
   if (causal) kmask_from_v = min(kmask_from_v, qw0 + p.causal_off - SUB + 1);
@@ -200,7 +206,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   // arithmetic.  Rows past the end of the keys re-read the last key (they are masked later):
   // the last, possibly partial, tile has its own clamped offsets, and tiles beyond it (the
   // ring runs ahead of the loop) re-read the last tile.
-  const int last_tile = (p.Sk - 1) / kBN;
+  const int last_tile = (p.Sk - 1) / BN;
   unsigned k_off[IPW], v_off[IPW], k_off_last[IPW], v_off_last[IPW];
 #pragma unroll
   for (int i = 0; i < IPW; i++) {
@@ -208,7 +214,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     const int kc = (pc ^ ((row / (256 / RB)) % CPR)) * 8;
     const int vswz = (D == 128) ? ((row & 3) << 1) : (row & 2);
     const int vc = ((((pc >> 1) ^ vswz) << 1) | (pc & 1)) * 8;
-    const int row_last = max(0, min(row, p.Sk - 1 - last_tile * kBN));
+    const int row_last = max(0, min(row, p.Sk - 1 - last_tile * BN));
     k_off[i] = (unsigned)(((int64_t)row * p.k_ss + kc) * 2);
     v_off[i] = (unsigned)(((int64_t)row * p.v_ss + vc) * 2);
     k_off_last[i] = (unsigned)(((int64_t)row_last * p.k_ss + kc) * 2);
@@ -226,7 +232,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   // stops advancing at the last tile (later issues re-read it with the clamped offsets).
   const __bf16* k_next = uniform_ptr(kg);
   const __bf16* v_next = uniform_ptr(vg);
-  const int64_t k_tile_stride = (int64_t)kBN * p.k_ss, v_tile_stride = (int64_t)kBN * p.v_ss;
+  const int64_t k_tile_stride = (int64_t)BN * p.k_ss, v_tile_stride = (int64_t)BN * p.v_ss;
   int k_left = last_tile, v_left = last_tile;  // tiles still ahead of the pointer
   auto issue_k = [&](int slot) __attribute__((always_inline)) {
     const bool last = k_left <= 0;
@@ -437,50 +443,68 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   __builtin_amdgcn_s_waitcnt(0);
   wg_barrier();  // B_0
 
-  // Ring protocol.  Sub-tile j = 2u + kt lives in tile u.  K_u is read in steps 2u-2 .. 2u
-  // (step 2u-2 only prefetches), V_u in steps 2u+1 and 2u+2.  Barrier B_u sits in front of
-  // step 2u.  Right after B_w every wave issues the loads of K_{w+3} and V_{w+2} into the
-  // slots K_{w-1} and V_{w-2} vacated (all waves are past step 2w-1); they are first read in
-  // step 2w+4, so each wave waits for its share (all but the newest 2*IPW loads, in order)
+  // Ring protocol.  Sub-tile j = NSUB*u + kt lives in tile u.  Step j reads the V operands of
+  // sub-tile j-1 and the K operands of sub-tile j+2, so K_u is read in steps NSUB*u-2 ..
+  // NSUB*(u+1)-3 and V_u in steps NSUB*u+1 .. NSUB*(u+1).  Barrier B_u sits in front of step
+  // NSUB*u.  Right after B_w every wave issues the loads of K_{w+3} and V_{w+2} into the slots
+  // K_{w-1} and V_{w-2} vacated (all waves are past step NSUB*w-1); they are first read two
+  // tiles later, so each wave waits for its share (all but the newest 2*IPW loads, in order)
   // right before B_{w+2}.
   // S and P alternate between two register sets: even steps read sA / pB and write sB / pA,
   // odd steps the other way round, so no step has to copy its results.
   f32x16 sA, sB;
   bf16x8 pA[2], pB[2];
-  constexpr unsigned kKt1 = SUB * RB;  // byte offset of the second sub-tile inside a tile
+  constexpr unsigned SUBB = SUB * RB;  // bytes of one sub-tile inside a tile
+  // Step NSUB*u + kt of the tile in ring slot `su` (previous tile in sp, next in sn).
+  auto tile_step = [&](int u, auto su_c, auto kt_c) __attribute__((always_inline)) {
+    constexpr int su = decltype(su_c)::value, kt = decltype(kt_c)::value;
+    constexpr int sp = (su + NS - 1) % NS, sn = (su + 1) % NS;
+    constexpr unsigned v_imm = kt == 0 ? sp * TILE_BYTES + (NSUB - 1) * SUBB : su * TILE_BYTES + (kt - 1) * SUBB;
+    constexpr unsigned k_imm = kt + 2 < NSUB ? su * TILE_BYTES + (kt + 2) * SUBB : sn * TILE_BYTES + (kt + 2 - NSUB) * SUBB;
+    const int j = NSUB * u + kt;
+    if (j <= (kt == 0 ? jw_first : jw_in)) {
+      if (kt % 2 == 0) step(j * SUB, IC<0>{}, IC<(int)v_imm>{}, IC<(int)k_imm>{}, sA, sB, pB, pA);
+      else step(j * SUB, IC<0>{}, IC<(int)v_imm>{}, IC<(int)k_imm>{}, sB, sA, pA, pB);
+    }
+  };
   if (n_tiles > 0) {
     issue_k(3 % NS);
     issue_v(2 % NS);
     if (jw > 0) {
-      // S_0 = K_0[0:32] Q^T, plain (nothing to overlap with yet); operands of step 0 (K_0, kt 1)
+      // S_0 = K_0[0:32] Q^T, plain (nothing to overlap with yet); operands of step 0 (sub-tile 1)
 #pragma unroll
       for (int i = 0; i < 16; i++) sA[i] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_k(ks, 0), qf[ks], sA, 0, 0, 0);
 #pragma unroll
-      for (int ks = 0; ks < KS; ks++) pre[ks] = load_k(ks, kKt1);
-      // step 0: S_1 from (K_0, kt 1) alongside the softmax of sub-tile 0; prefetch (K_1, kt 0)
-      step(0, IC<1>{}, IC<0>{}, IC<1 * TILE_BYTES>{}, sA, sB, pB, pA);
-      // step 1: PV of sub-tile 0 (V_0, kt 0), S_2 from (K_1, kt 0), softmax of sub-tile 1; prefetch (K_1, kt 1)
-      if (1 <= jw) step(SUB, IC<0>{}, IC<0>{}, IC<1 * TILE_BYTES + kKt1>{}, sB, sA, pA, pB);
+      for (int ks = 0; ks < KS; ks++) pre[ks] = load_k(ks, SUBB);
+      // step 0: S_1 alongside the softmax of sub-tile 0 (no PV yet); prefetch the K operands of sub-tile 2
+      constexpr unsigned k_imm0 = 2 < NSUB ? 2 * SUBB : 1 * TILE_BYTES;
+      step(0, IC<1>{}, IC<0>{}, IC<(int)k_imm0>{}, sA, sB, pB, pA);
+      // the other steps of tile 0 (tiles 0 and 1 sit in ring slots 0 and 1)
+      tile_step(0, IC<0>{}, IC<1>{});
+      if constexpr (NSUB > 2) {
+        tile_step(0, IC<0>{}, IC<2>{});
+        tile_step(0, IC<0>{}, IC<3>{});
+      }
     }
   }
-  // tiles u = 1 .. n_tiles: steps 2u and 2u+1 (the last tile index only has step 2u, which
-  // folds in the PV product of the final sub-tile; its softmax sees only masked keys)
+  // tiles u = 1 .. n_tiles: steps NSUB*u .. NSUB*u + NSUB-1 (the last tile index only has its first
+  // step, which folds in the PV product of the final sub-tile; its softmax sees only masked keys)
   auto tile_body = [&](int u, auto slot_c) __attribute__((always_inline)) {   // slot_c = u % NS
-    constexpr int su = decltype(slot_c)::value, sp = (su + NS - 1) % NS, sn = (su + 1) % NS;
+    constexpr int su = decltype(slot_c)::value;
     __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * IPW));  // vmcnt only
     wg_barrier();                                    // B_u
     issue_k((su + 3) % NS);   // K_{u+3}
     issue_v((su + 2) % NS);   // V_{u+2}
-    // step 2u: S of sub-tile 2u+1 (K_u, kt 1, already in `pre`); PV of sub-tile 2u-1 (V_{u-1}, kt 1);
-    //          softmax of sub-tile 2u; prefetch (K_{u+1}, kt 0)
-    if (2 * u <= jw_even) step(2 * u * SUB, IC<0>{}, IC<sp * TILE_BYTES + kKt1>{}, IC<sn * TILE_BYTES>{}, sA, sB, pB, pA);
-    // step 2u+1: S of sub-tile 2u+2 (K_{u+1}, kt 0); PV of sub-tile 2u (V_u, kt 0);
-    //          softmax of sub-tile 2u+1; prefetch (K_{u+1}, kt 1)
-    if (2 * u + 1 <= jw_odd)
-      step((2 * u + 1) * SUB, IC<0>{}, IC<su * TILE_BYTES>{}, IC<sn * TILE_BYTES + kKt1>{}, sB, sA, pA, pB);
+    tile_step(u, slot_c, IC<0>{});
+    tile_step(u, slot_c, IC<1>{});
+    if constexpr (NSUB > 2) {
+      tile_step(u, slot_c, IC<2>{});
+      tile_step(u, slot_c, IC<3>{});
+    }
   };
+  static_assert(NSUB == 2 || NSUB == 4, "tile_body spells out 2 or 4 steps");
   for (int u0 = 0; u0 <= n_tiles; u0 += NS) {
     if (u0 >= 1) tile_body(u0, IC<0>{});
     if (u0 + 1 <= n_tiles) tile_body(u0 + 1, IC<1 % NS>{});
@@ -582,7 +606,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
 template <int D, int EPI>
 hipError_t launch_one(const AttnParams& p, dim3 grid, hipStream_t stream) {
   // K/V rings; the epilogue reuses them for kWaves private 32 x D fp32 tiles plus 32 lse each
-  constexpr int ring_bytes = 2 * kRing * kBN * 2 * D;
+  constexpr int ring_bytes = 2 * kRing * tile_keys<D>() * 2 * D;
   constexpr int epi_bytes = kWaves * 32 * 4 * D + kWaves * 32 * 4;
   constexpr int lds_bytes = ring_bytes > epi_bytes ? ring_bytes : epi_bytes;
   static_assert(lds_bytes <= 160 * 1024, "LDS budget of one CU exceeded");
