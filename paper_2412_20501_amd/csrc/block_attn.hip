@@ -550,14 +550,15 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     // Out, Lse <- Update(block_out, block_lse) on the accumulators p.out / p.lse.  All of the
     // wave's accumulator rows are fetched first (the O registers are free by now), so their
     // latencies overlap instead of each load waiting behind the previous row's store.  Rows
-    // past Sq fetch the last valid row and are never stored.
+    // past Sq fetch the last valid row and are never stored.  The accumulator is touched once
+    // per launch, so it is read and written past the caches (non-temporal).
     float* const acc_out = reinterpret_cast<float*>(p.out);
     f32x4 x[NIT];
     float la[NIT];
 #pragma unroll
     for (int it = 0; it < NIT; it++) {
       const int grow = min(qw0 + it * RPI_OUT + rr, p.Sq - 1);
-      x[it] = *reinterpret_cast<const f32x4*>(acc_out + o_bh + (int64_t)grow * p.o_ss);
+      x[it] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(acc_out + o_bh + (int64_t)grow * p.o_ss));
       la[it] = p.lse[l_bh + (int64_t)grow * p.l_ss];
     }
 #pragma unroll
@@ -567,7 +568,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
       const f32x4 o = *reinterpret_cast<const f32x4*>(my + r * ROWB + ((cc ^ (r & 15)) << 4));
       const UpdatePlan pl = plan_update(la[it], my_lse[r]);
       if (grow < p.Sq) {
-        *reinterpret_cast<f32x4*>(acc_out + o_bh + (int64_t)grow * p.o_ss) = apply_update(pl, x[it], o);
+        __builtin_nontemporal_store(apply_update(pl, x[it], o), reinterpret_cast<f32x4*>(acc_out + o_bh + (int64_t)grow * p.o_ss));
         // every lane of the row took the old lse in the first loop, so the single write is safe
         if (cc == 0) p.lse[l_bh + (int64_t)grow * p.l_ss] = pl.new_lse;
       }
