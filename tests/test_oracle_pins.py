@@ -309,6 +309,21 @@ def test_other_orders_cover_every_needed_pair_once():
     assert [kv for q, kv in oracle.ring_attention_order(4, False) if q == 1] == [1, 0, 3, 2]
 
 
+def test_orders_cover_pairs_for_every_small_device_count():
+    for n in range(1, 13):
+        full = [(c, j) for c in range(n) for j in range(n)]
+        assert sorted((c, j) for _, j, c in oracle.ring_schedule(n, False)) == full
+        assert sorted(oracle.ring_attention_order(n, False)) == full
+        assert sorted(oracle.zigzag_order(n)) == _causal_pairs(2 * n)
+        assert len(oracle.zigzag_order(n)) == n * (2 * n + 1)
+        for per_node in (d for d in range(1, n + 1) if n % d == 0):
+            assert sorted(oracle.hybrid_order(n // per_node, per_node, False)) == full
+            assert sorted(oracle.hybrid_order(n // per_node, per_node, True)) == _causal_pairs(n)
+        # every device of the zigzag partition owns the same amount of causal work: 2N + 1 segment pairs
+        for a, b in oracle.zigzag_segments(n):
+            assert (a + 1) + (b + 1) == 2 * n + 1
+
+
 def test_hybrid_degenerates_to_its_two_ingredients():
     for causal in (False, True):
         # one node: plain Algorithm 1; one device per node: plain Ring Attention
