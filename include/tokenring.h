@@ -202,6 +202,19 @@ tr_status tr_ring_attn_sched(const tr_tensor* q, const tr_tensor* k, const tr_te
                              int n_devices, int causal, int schedule, int n_inner,
                              const tr_tensor* out, const tr_tensor* lse, float scale, void* hip_stream);
 
+/*
+ * Host-only view of what tr_ring_attn_sched (and the fused tr_ring_attn, schedule
+ * TR_SCHED_TOKENRING) will run: the block steps of a schedule in execution order.  Returns
+ * the number of steps, or -1 on invalid arguments (tr_last_error() says why).  If steps_out
+ * (HOST memory, 3 * capacity int32) is given, step i < capacity is written as
+ *   steps_out[3i] = Query segment, steps_out[3i+1] = K/V segment, steps_out[3i+2] = index of
+ *   the attention launch that carries the step
+ * (steps of one launch touch distinct Query segments and run concurrently; launches run in
+ * order).  Segments are n_devices equal chunks of S, 2 * n_devices for TR_SCHED_ZIGZAG; with
+ * causal != 0 a step with equal segments is the diagonal-masked one.  Touches no device.
+ */
+int64_t tr_schedule_steps(int schedule, int n_devices, int n_inner, int causal, int32_t* steps_out, int64_t capacity);
+
 /* Bytes of workspace the two-kernel form of tr_ring_attn needs for these shapes (0 on invalid arguments). */
 size_t tr_ring_attn_workspace_bytes(const tr_tensor* q, int n_chunks);
 

@@ -72,6 +72,8 @@ def _load():
     lib.tr_ring_attn_blocks.restype = ctypes.c_int
     lib.tr_ring_attn_blocks_workspace_bytes.argtypes = [P, ctypes.c_int, ctypes.c_int]
     lib.tr_ring_attn_blocks_workspace_bytes.restype = ctypes.c_size_t
+    lib.tr_schedule_steps.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int32), ctypes.c_int64]
+    lib.tr_schedule_steps.restype = ctypes.c_int64
     lib.tr_ring_attn_workspace_bytes.argtypes = [P, ctypes.c_int]
     lib.tr_ring_attn_workspace_bytes.restype = ctypes.c_size_t
     lib.tr_last_error.argtypes = []
@@ -199,6 +201,16 @@ def tr_ring_attn_blocks(q, k, v, n_chunks, causal, out, lse, block_dtype, worksp
     _check(_lib.tr_ring_attn_blocks(desc(q), desc(k), desc(v), int(n_chunks), int(bool(causal)), desc(out), desc(lse),
                                     float(scale), int(block_dtype), workspace.data_ptr(),
                                     workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def tr_schedule_steps(schedule, n_devices, causal, n_inner=1):
+    """The block steps of a schedule in execution order: a list of (q_segment, kv_segment, launch_index)."""
+    n = int(_lib.tr_schedule_steps(int(schedule), int(n_devices), int(n_inner), int(bool(causal)), None, 0))
+    if n < 0:
+        raise TokenRingError(-1, _lib.tr_last_error().decode())
+    buf = (ctypes.c_int32 * (3 * max(n, 1)))()
+    _lib.tr_schedule_steps(int(schedule), int(n_devices), int(n_inner), int(bool(causal)), buf, n)
+    return [(buf[3 * i], buf[3 * i + 1], buf[3 * i + 2]) for i in range(n)]
 
 
 def tr_ring_attn_workspace_bytes(q, n_chunks) -> int:

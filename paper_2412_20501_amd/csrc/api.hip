@@ -205,20 +205,21 @@ int build_schedule(int schedule, int n, int n_inner, bool causal, std::vector<Ri
   }
 }
 
-// Runs the steps in order with the Update fused into the attention epilogue.  Consecutive steps
-// that touch distinct Query segments and are of one kind (first block of their segment, which
-// is written, or a later block, which is merged) are independent of each other - they are what
-// different devices compute at the same time - and go out as one launch.
-tr_status run_steps_fused(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, const tr_tensor* out, const tr_tensor* lse,
-                          int n_seg, bool causal, float scale, const std::vector<RingStep>& steps, void* stream) {
-  const int64_t C = q->S / n_seg;
-  const tr_tensor q0 = chunk_view(q, 0, C), k0 = chunk_view(k, 0, C), v0 = chunk_view(v, 0, C);
-  const tr_tensor o0 = chunk_view(out, 0, C), l0 = chunk_view(lse, 0, C);
+// One launch of the fused forms: steps [begin, end) of the list; `merge` = the blocks are merged
+// into accumulators that already hold a result (otherwise they are each segment's first block).
+struct LaunchGroup { size_t begin, end; bool merge; };
+
+// Splits the step list into launches.  Consecutive steps that touch distinct Query segments and
+// are of one kind (first block of their segment, which is written, or a later block, which is
+// merged) are independent of each other - they are what different devices compute at the same
+// time - and share a launch (at most kAttnGroupMax steps).
+std::vector<LaunchGroup> group_steps(const std::vector<RingStep>& steps, int n_seg) {
+  std::vector<LaunchGroup> groups;
   std::vector<char> started((size_t)n_seg, 0);  // has this Query segment received its first block?
   std::vector<int> in_group((size_t)n_seg, -1); // index of the group that last used the segment
   size_t pos = 0;
-  int group_id = 0;
   while (pos < steps.size()) {
+    const int group_id = (int)groups.size();
     const bool merge = started[(size_t)steps[pos].qs] != 0;
     size_t end = pos;
     while (end < steps.size() && (int)(end - pos) < tr::kAttnGroupMax && (started[(size_t)steps[end].qs] != 0) == merge &&
@@ -226,12 +227,23 @@ tr_status run_steps_fused(const tr_tensor* q, const tr_tensor* k, const tr_tenso
       in_group[(size_t)steps[end].qs] = group_id;
       end++;
     }
-    const StepGroup g = {steps.data() + pos, (int)(end - pos), C, causal};
-    const tr_status st = attn_common(&q0, &k0, &v0, 0, 0, scale, &o0, &l0, stream, merge, &g);
-    if (st != TR_OK) return st;
     for (size_t i = pos; i < end; i++) started[(size_t)steps[i].qs] = 1;
+    groups.push_back({pos, end, merge});
     pos = end;
-    group_id++;
+  }
+  return groups;
+}
+
+// Runs the steps in order with the Update fused into the attention epilogue, one launch per group.
+tr_status run_steps_fused(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, const tr_tensor* out, const tr_tensor* lse,
+                          int n_seg, bool causal, float scale, const std::vector<RingStep>& steps, void* stream) {
+  const int64_t C = q->S / n_seg;
+  const tr_tensor q0 = chunk_view(q, 0, C), k0 = chunk_view(k, 0, C), v0 = chunk_view(v, 0, C);
+  const tr_tensor o0 = chunk_view(out, 0, C), l0 = chunk_view(lse, 0, C);
+  for (const LaunchGroup& grp : group_steps(steps, n_seg)) {
+    const StepGroup g = {steps.data() + grp.begin, (int)(grp.end - grp.begin), C, causal};
+    const tr_status st = attn_common(&q0, &k0, &v0, 0, 0, scale, &o0, &l0, stream, grp.merge, &g);
+    if (st != TR_OK) return st;
   }
   return TR_OK;
 }
@@ -507,6 +519,29 @@ tr_status tr_ring_attn_blocks(const tr_tensor* q, const tr_tensor* k, const tr_t
   if (block_dtype != TR_F32 && block_dtype != TR_BF16) return fail(TR_ERR_DTYPE, "block_dtype %d is neither fp32 nor bf16", block_dtype);
   if (!workspace) return fail(TR_ERR_WORKSPACE, "the two-kernel form needs a workspace");
   return ring_attn_impl(q, k, v, n_chunks, causal, out, lse, scale, block_dtype, workspace, workspace_bytes, hip_stream);
+}
+
+int64_t tr_schedule_steps(int schedule, int n_devices, int n_inner, int causal, int32_t* steps_out, int64_t capacity) {
+  g_err[0] = 0;
+  if (n_devices < 1 || n_devices > 4096) { fail(TR_ERR_SHAPE, "n_devices %d out of range [1, 4096]", n_devices); return -1; }
+  if (schedule < TR_SCHED_TOKENRING || schedule > TR_SCHED_HYBRID) { fail(TR_ERR_UNSUPPORTED, "unknown schedule %d", schedule); return -1; }
+  if (schedule == TR_SCHED_ZIGZAG && !causal) { fail(TR_ERR_UNSUPPORTED, "the zigzag partition only exists for the causal case"); return -1; }
+  if (schedule == TR_SCHED_HYBRID && (n_inner < 1 || n_devices % n_inner)) {
+    fail(TR_ERR_SHAPE, "hybrid schedule: n_inner %d must divide n_devices %d", n_inner, n_devices);
+    return -1;
+  }
+  std::vector<RingStep> steps;
+  const int n_seg = build_schedule(schedule, n_devices, n_inner, causal != 0, steps);
+  if (steps_out && capacity > 0) {
+    const std::vector<LaunchGroup> groups = group_steps(steps, n_seg);
+    for (size_t g = 0; g < groups.size(); g++)
+      for (size_t i = groups[g].begin; i < groups[g].end && (int64_t)i < capacity; i++) {
+        steps_out[3 * i] = steps[i].qs;
+        steps_out[3 * i + 1] = steps[i].ks;
+        steps_out[3 * i + 2] = (int32_t)g;
+      }
+  }
+  return (int64_t)steps.size();
 }
 
 tr_status tr_ring_attn_sched(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int n_devices, int causal,

@@ -27,7 +27,7 @@ def _t(tr, dtype, B, H, S, D, ptr=0x7F0000000000, strides=None):
 def test_every_declared_symbol_is_exported(tr):
     text = open(HEADER).read()
     names = set(re.findall(r"\b(tr_[a-z_]+)\s*\(", text))
-    assert {"tr_block_attn", "tr_block_attn_causal_at", "tr_block_attn_merge", "tr_merge", "tr_merge_n", "tr_ring_attn", "tr_ring_attn_blocks", "tr_ring_attn_blocks_workspace_bytes", "tr_ring_attn_sched",
+    assert {"tr_block_attn", "tr_block_attn_causal_at", "tr_block_attn_merge", "tr_merge", "tr_merge_n", "tr_ring_attn", "tr_ring_attn_blocks", "tr_ring_attn_blocks_workspace_bytes", "tr_ring_attn_sched", "tr_schedule_steps",
             "tr_ring_attn_workspace_bytes", "tr_time_next_kernel", "tr_probe_mfma", "tr_last_error", "tr_version"} <= names
     lib = ctypes.CDLL(tr.LIB_PATH)
     for n in names:
