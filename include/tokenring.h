@@ -143,7 +143,9 @@ tr_status tr_merge_n(const tr_tensor* out, const tr_tensor* lse,
  *   q [B,Hq,S,D] bf16   k, v [B,Hkv,S,D] bf16   out [B,Hq,S,D] fp32   lse [B,Hq,S] fp32
  *   S must be a multiple of n_chunks; n_chunks >= 1; scale <= 0 selects 1/sqrt(D).
  *   workspace == NULL (workspace_bytes ignored): every step after a Query chunk's first one
- *   runs as tr_block_attn_merge, i.e. the Update happens in the attention kernel's epilogue.
+ *   runs as tr_block_attn_merge, i.e. the Update happens in the attention kernel's epilogue;
+ *   consecutive steps on distinct Query chunks (what different devices do at the same time)
+ *   share one kernel launch (tr_schedule_steps shows the grouping).
  *   workspace != NULL: the two-kernel form of Algorithm 1 - tr_block_attn writes one fp32
  *   block result (block_out, block_lse) into the workspace and tr_merge folds it into
  *   out/lse.  It needs at least tr_ring_attn_workspace_bytes(q, n_chunks) bytes, 256-byte
