@@ -17,6 +17,8 @@
  *     layout can be passed through the strides.)
  *   - `hip_stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work on
  *     it and return without synchronising.
+ *   - A tensor a call writes (out, lse, out_acc, lse_acc) must not overlap itself: a stride of 0
+ *     or one smaller than what lies inside it on a dimension larger than 1 is TR_ERR_STRIDE.
  *   - Every call validates its arguments first; on an error nothing is launched, the
  *     status is returned and tr_last_error() describes it.  No exception crosses the ABI.
  *   - Grouped-query attention: q.H must be a multiple of k.H; query head h reads K/V
@@ -110,7 +112,7 @@ tr_status tr_block_attn_merge(const tr_tensor* q, const tr_tensor* k, const tr_t
  * identity element (out = 0, lse = -inf) on either side is exact and never yields NaN.
  *   out_acc   [B,H,S,D] fp32 (read + written)    lse_acc   [B,H,S] fp32 (read + written)
  *   block_out [B,H,S,D] fp32 or bf16 (read)      block_lse [B,H,S] fp32 (read)
- * D must be a multiple of 4 (fp32 block) or 8 (bf16 block); any S (0 allowed).
+ * D must be a multiple of 4 (fp32 and bf16 blocks alike); any S (0 allowed).
  * The accumulator tensors must not overlap the block tensors (TR_ERR_ALIAS).
  */
 tr_status tr_merge(const tr_tensor* out_acc, const tr_tensor* lse_acc,
@@ -127,7 +129,7 @@ tr_status tr_merge(const tr_tensor* out_acc, const tr_tensor* lse_acc,
  *   block_outs[i] [B,H,S,D] fp32 or bf16 (one dtype for all), block_lses[i] [B,H,S] fp32, i < n,
  *     1 <= n <= 16: host arrays of n descriptor pointers; all partials share their strides.
  * A partial row with lse = -inf has weight 0 and its out values are ignored; if every partial
- * of a row is empty the result is out = 0, lse = -inf.  D multiple of 4 (fp32) or 8 (bf16).
+ * of a row is empty the result is out = 0, lse = -inf.  D must be a multiple of 4.
  * The partials must not overlap out / lse (TR_ERR_ALIAS).
  */
 tr_status tr_merge_n(const tr_tensor* out, const tr_tensor* lse,
@@ -230,27 +232,11 @@ size_t tr_ring_attn_workspace_bytes(const tr_tensor* q, int n_chunks);
  */
 tr_status tr_time_next_kernel(void* start_event, void* stop_event);
 
-/*
- * Measurement aid (no operation of the paper): launches a kernel that only issues dense
- * 32x32x16 bf16 MFMAs, 8 waves per workgroup, on `n_blocks` workgroups, each wave running
- * 8 * iters MFMAs that rotate through 8 operand pairs read from `operands` (device, 16 KiB:
- * 16 fragments of 64 lanes x 8 bf16, first the 8 A then the 8 B fragments, 16-byte aligned;
- * the values are the caller's choice, e.g. the distribution of the real workload).  Timed
- * with tr_time_next_kernel it gives the MFMA rate the chip sustains for that data, the
- * practical ceiling next to which an MFMA-bound kernel can be read.  idle in {0, 1, 2, 4, 8}:
- * every wave additionally sleeps 64 * idle cycles after each 8 MFMAs, which lowers the duty
- * cycle of the MFMA pipe with no other work added (how the sustained clock responds to the
- * duty cycle alone).  `sink` (device, >= 4 bytes) is only there to keep the results live.
- * *flop_out (host, may be NULL) receives the flop count of the launch.  Enqueues on hip_stream
- * and returns without synchronising.
- */
-tr_status tr_probe_mfma(const void* operands, size_t operand_bytes, void* sink, int iters, int idle, int n_blocks,
-                        double* flop_out, void* hip_stream);
-
 /* Description of the last error on the calling thread ("" if none). Static storage. */
 const char* tr_last_error(void);
 
-/* Library version string, e.g. "tokenring-gfx950 0.1". Static storage. */
+/* Library version string, "tokenring-gfx950 <version> (sources <16 hex digits>)": the digits are a hash of
+ * the kernel sources, headers and compiler flags the library was built from.  Static storage. */
 const char* tr_version(void);
 
 #ifdef __cplusplus

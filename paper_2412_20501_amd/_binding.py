@@ -59,9 +59,6 @@ def _load():
     lib.tr_ring_attn.restype = ctypes.c_int
     lib.tr_time_next_kernel.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
     lib.tr_time_next_kernel.restype = ctypes.c_int
-    lib.tr_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                  ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
-    lib.tr_probe_mfma.restype = ctypes.c_int
     lib.tr_merge_n.argtypes = [P, P, ctypes.POINTER(P), ctypes.POINTER(P), ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     lib.tr_merge_n.restype = ctypes.c_int
     lib.tr_ring_attn_sched.argtypes = [P, P, P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P, ctypes.c_float,
@@ -176,14 +173,6 @@ def tr_time_next_kernel(start_event, stop_event):
             ev.record()
         return ev.cuda_event
     _check(_lib.tr_time_next_kernel(handle(start_event), handle(stop_event)))
-
-
-def tr_probe_mfma(operands, sink, iters, n_blocks, idle=0, stream=None) -> float:
-    """MFMA-only measurement kernel on bf16 `operands` (>= 8192 elements); returns the launch's flop count."""
-    flop = ctypes.c_double(0.0)
-    _check(_lib.tr_probe_mfma(operands.data_ptr(), operands.numel() * operands.element_size(), sink.data_ptr(),
-                              int(iters), int(idle), int(n_blocks), ctypes.byref(flop), _stream(stream)))
-    return flop.value
 
 
 def tr_ring_attn_sched(q, k, v, n_devices, causal, schedule, out, lse, scale=0.0, n_inner=1, stream=None):

@@ -62,6 +62,29 @@ tr_status check_tensor(const char* name, const tr_tensor* t, bool allow_bf16, bo
   return TR_OK;
 }
 
+// A tensor the kernels write must not address one element through two index tuples (a zero or
+// too small stride on a dimension larger than 1): rows are updated by different waves, so an
+// overlapping view would race.  Sufficient test: ordered by stride, every dimension must step
+// over the whole extent of the dimensions inside it.
+tr_status check_written(const char* name, const tr_tensor* t) {
+  if (extent_elems(t) == 0) return TR_OK;
+  int64_t size[3] = {t->B, t->H, t->S}, stride[3] = {t->stride_b, t->stride_h, t->stride_s};
+  for (int i = 0; i < 3; i++)
+    for (int j = i + 1; j < 3; j++)
+      if (stride[j] < stride[i]) {
+        const int64_t a = size[i], b = stride[i];
+        size[i] = size[j]; stride[i] = stride[j];
+        size[j] = a; stride[j] = b;
+      }
+  int64_t inner = t->D;
+  for (int i = 0; i < 3; i++) {
+    if (size[i] <= 1) continue;
+    if (stride[i] < inner) return fail(TR_ERR_STRIDE, "%s: a written tensor must not overlap itself (stride %lld < %lld elements inside it)", name, (long long)stride[i], (long long)inner);
+    inner = stride[i] * (size[i] - 1) + inner;
+  }
+  return TR_OK;
+}
+
 // One block step of a schedule: Query segment qs attends K/V segment ks (equal segments of S).
 struct RingStep { int qs, ks; };
 
@@ -85,6 +108,7 @@ tr_status attn_common(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v
   if ((st = check_tensor("v", v, true, false, 16)) != TR_OK) return st;
   if ((st = check_tensor("out", out, !fuse_update, true, 16)) != TR_OK) return st;
   if ((st = check_tensor("lse", lse, false, true, 4)) != TR_OK) return st;
+  if ((st = check_written("out", out)) != TR_OK || (st = check_written("lse", lse)) != TR_OK) return st;
   if (q->D != 64 && q->D != 128) return fail(TR_ERR_SHAPE, "head dim %lld not supported (64 or 128)", (long long)q->D);
   if (k->D != q->D || v->D != q->D || out->D != q->D) return fail(TR_ERR_SHAPE, "head dims of q, k, v, out differ");
   if (lse->D != 1) return fail(TR_ERR_SHAPE, "lse must have D = 1");
@@ -271,24 +295,13 @@ tr_status tr_time_next_kernel(void* start_event, void* stop_event) {
   g_timing.stop = static_cast<hipEvent_t>(stop_event);
   return TR_OK;
 }
-tr_status tr_probe_mfma(const void* operands, size_t operand_bytes, void* sink, int iters, int idle, int n_blocks,
-                        double* flop_out, void* hip_stream) {
-  g_err[0] = 0;
-  if (!operands || !sink) return fail(TR_ERR_NULL, "tr_probe_mfma: operands and sink must not be NULL");
-  if (operand_bytes < (size_t)tr::mfma_probe_operand_bytes())
-    return fail(TR_ERR_SHAPE, "tr_probe_mfma: %zu operand bytes given, %d needed", operand_bytes, tr::mfma_probe_operand_bytes());
-  if (((uintptr_t)operands & 15) != 0) return fail(TR_ERR_STRIDE, "tr_probe_mfma: operands must be 16-byte aligned");
-  if (iters < 1 || iters > (1 << 24) || n_blocks < 1 || n_blocks > (1 << 20))
-    return fail(TR_ERR_SHAPE, "tr_probe_mfma: iters %d / n_blocks %d out of range", iters, n_blocks);
-  if (idle != 0 && idle != 1 && idle != 2 && idle != 4 && idle != 8) return fail(TR_ERR_UNSUPPORTED, "tr_probe_mfma: idle must be 0, 1, 2, 4 or 8 (got %d)", idle);
-  const hipError_t e = tr::launch_mfma_probe(operands, static_cast<float*>(sink), iters, idle, n_blocks, static_cast<hipStream_t>(hip_stream));
-  if (e != hipSuccess) return fail(TR_ERR_HIP, "tr_probe_mfma: launch failed: %s", hipGetErrorString(e));
-  // waves per block * MFMAs per wave * flop per 32x32x16 MFMA
-  if (flop_out) *flop_out = (double)n_blocks * (tr::mfma_probe_threads() / 64) * 8.0 * iters * 32768.0;
-  return TR_OK;
-}
-
-const char* tr_version(void) { return "tokenring-gfx950 0.1"; }
+#ifndef TR_SOURCE_HASH_STR
+#define TR_SOURCE_HASH_STR "0000000000000000"
+#endif
+// The tagged string is also what the build script looks for inside the binary to decide whether
+// the library was compiled from the sources on disk.
+__attribute__((used)) static const char tr_source_hash_tag[] = "TR_SOURCE_HASH=" TR_SOURCE_HASH_STR;
+const char* tr_version(void) { return "tokenring-gfx950 0.2 (sources " TR_SOURCE_HASH_STR ")"; }
 
 tr_status tr_block_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int mask_kind, float scale,
                         const tr_tensor* out, const tr_tensor* lse, void* hip_stream) {
@@ -324,6 +337,7 @@ tr_status tr_merge(const tr_tensor* out_acc, const tr_tensor* lse_acc, const tr_
   if ((st = check_tensor("block_out", block_out, true, true, 8)) != TR_OK) return st;
   if ((st = check_tensor("block_lse", block_lse, false, true, 4)) != TR_OK) return st;
   if (block_out->dtype == TR_F32 && (st = check_tensor("block_out", block_out, true, true, 16)) != TR_OK) return st;
+  if ((st = check_written("out_acc", out_acc)) != TR_OK || (st = check_written("lse_acc", lse_acc)) != TR_OK) return st;
   if (lse_acc->D != 1 || block_lse->D != 1) return fail(TR_ERR_SHAPE, "lse tensors must have D = 1");
   if (out_acc->D % 4) return fail(TR_ERR_SHAPE, "D = %lld must be a multiple of 4", (long long)out_acc->D);
   if (block_out->B != out_acc->B || block_out->H != out_acc->H || block_out->S != out_acc->S || block_out->D != out_acc->D)
@@ -362,6 +376,7 @@ tr_status tr_merge_n(const tr_tensor* out, const tr_tensor* lse, const tr_tensor
   if (n < 1 || n > tr::kMergeNMax) return fail(TR_ERR_SHAPE, "n = %d partials out of range [1, %d]", n, tr::kMergeNMax);
   if ((st = check_tensor("out", out, false, true, 16)) != TR_OK) return st;
   if ((st = check_tensor("lse", lse, false, true, 4)) != TR_OK) return st;
+  if ((st = check_written("out", out)) != TR_OK || (st = check_written("lse", lse)) != TR_OK) return st;
   if (lse->D != 1) return fail(TR_ERR_SHAPE, "lse tensors must have D = 1");
   if (out->D % 4) return fail(TR_ERR_SHAPE, "D = %lld must be a multiple of 4", (long long)out->D);
   if (lse->B != out->B || lse->H != out->H || lse->S != out->S) return fail(TR_ERR_SHAPE, "lse shape does not match out");
@@ -381,7 +396,6 @@ tr_status tr_merge_n(const tr_tensor* out, const tr_tensor* lse, const tr_tensor
     if (bo->stride_b != bo0->stride_b || bo->stride_h != bo0->stride_h || bo->stride_s != bo0->stride_s ||
         bl->stride_b != bl0->stride_b || bl->stride_h != bl0->stride_h || bl->stride_s != bl0->stride_s)
       return fail(TR_ERR_STRIDE, "partial %d: all partials must share their strides", i);
-    if (bo0->dtype == TR_BF16 && out->D % 8) return fail(TR_ERR_SHAPE, "D = %lld must be a multiple of 8 for bf16 partials", (long long)out->D);
     if (overlaps(out, bo) || overlaps(out, bl) || overlaps(lse, bo) || overlaps(lse, bl))
       return fail(TR_ERR_ALIAS, "partial %d overlaps the result tensors", i);
   }
@@ -443,6 +457,7 @@ tr_status ring_attn_impl(const tr_tensor* q, const tr_tensor* k, const tr_tensor
   if ((st = check_tensor("v", v, true, false, 16)) != TR_OK) return st;
   if ((st = check_tensor("out", out, false, true, 16)) != TR_OK) return st;
   if ((st = check_tensor("lse", lse, false, true, 4)) != TR_OK) return st;
+  if ((st = check_written("out", out)) != TR_OK || (st = check_written("lse", lse)) != TR_OK) return st;
   if (out->B != q->B || out->H != q->H || out->S != q->S || out->D != q->D || lse->B != q->B || lse->H != q->H || lse->S != q->S || lse->D != 1)
     return fail(TR_ERR_SHAPE, "out/lse shape does not match q");
 
@@ -566,6 +581,7 @@ tr_status tr_ring_attn_sched(const tr_tensor* q, const tr_tensor* k, const tr_te
   if ((st = check_tensor("v", v, true, false, 16)) != TR_OK) return st;
   if ((st = check_tensor("out", out, false, true, 16)) != TR_OK) return st;
   if ((st = check_tensor("lse", lse, false, true, 4)) != TR_OK) return st;
+  if ((st = check_written("out", out)) != TR_OK || (st = check_written("lse", lse)) != TR_OK) return st;
   if (out->B != q->B || out->H != q->H || out->S != q->S || out->D != q->D || lse->B != q->B || lse->H != q->H || lse->S != q->S || lse->D != 1)
     return fail(TR_ERR_SHAPE, "out/lse shape does not match q");
 

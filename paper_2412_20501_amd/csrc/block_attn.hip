@@ -226,7 +226,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   const unsigned lds_base = (unsigned)(unsigned long)(lptr_t)lds;
   auto dma16 = [&](const __bf16* base, unsigned off, unsigned lds_off) __attribute__((always_inline)) {
     const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + lds_off);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(off), "s"(base) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(off), "s"(base) : "memory", "m0");
   };
   // Tiles are issued strictly in order, so the tile base is a running wave-uniform pointer that
   // stops advancing at the last tile (later issues re-read it with the clamped offsets).

@@ -77,10 +77,6 @@ hipError_t launch_block_attn(const AttnParams& p, int D, int epilogue, hipStream
 hipError_t launch_merge(const MergeParams& p, bool blk_bf16, hipStream_t stream);
 hipError_t launch_merge_n(const MergeNParams& p, bool blk_bf16, hipStream_t stream);
 int attn_rows_per_block();  // query rows one attention workgroup covers
-// MFMA-only measurement kernel: n_blocks workgroups, each wave issuing 8 * iters MFMAs (32x32x16 bf16)
-hipError_t launch_mfma_probe(const void* operands, float* sink, int iters, int idle, int n_blocks, hipStream_t stream);
-int mfma_probe_threads();
-int mfma_probe_operand_bytes();
 
 // Events armed by tr_time_next_kernel for the calling thread; the next launch consumes them.
 struct TimingEvents { hipEvent_t start, stop; };

@@ -35,7 +35,6 @@ int main(void) {
   EXPECT(tr_ring_attn_workspace_bytes(&q, 4) == 2 * 16 * 128 * 4 + 256);   /* block_out, then block_lse rounded up to 256 B */
   EXPECT(tr_ring_attn_blocks_workspace_bytes(&q, 4, TR_BF16) == 2 * 16 * 128 * 2 + 256);
   EXPECT(tr_time_next_kernel(NULL, NULL) == TR_OK);
-  EXPECT(tr_probe_mfma(NULL, 0, NULL, 1, 0, 1, NULL, NULL) == TR_ERR_NULL);
   if (failures == 0) printf("c abi ok\n");
   return failures;
 }

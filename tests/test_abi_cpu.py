@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported(tr):
     text = open(HEADER).read()
     names = set(re.findall(r"\b(tr_[a-z_]+)\s*\(", text))
     assert {"tr_block_attn", "tr_block_attn_causal_at", "tr_block_attn_merge", "tr_merge", "tr_merge_n", "tr_ring_attn", "tr_ring_attn_blocks", "tr_ring_attn_blocks_workspace_bytes", "tr_ring_attn_sched", "tr_schedule_steps",
-            "tr_ring_attn_workspace_bytes", "tr_time_next_kernel", "tr_probe_mfma", "tr_last_error", "tr_version"} <= names
+            "tr_ring_attn_workspace_bytes", "tr_time_next_kernel", "tr_last_error", "tr_version"} <= names
     lib = ctypes.CDLL(tr.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in tokenring.h but not exported"
@@ -143,16 +143,65 @@ def test_merge_n_and_sched_reject_bad_arguments(tr):
     assert sched(oo=_t(tr, tr.TR_BF16, 1, 4, 4096, 128, ptr=0x7F3000000000))[0] == 2
 
 
-def test_probe_rejects_bad_arguments(tr):
+def test_written_tensors_must_not_overlap_themselves(tr):
+    """A zero or too small stride on a written tensor would let two waves update one element."""
     lib = tr.raw_lib()
-    ok_ptr, sink = 0x7F0000000000, 0x7F0000100000
-    assert lib.tr_probe_mfma(None, 16384, sink, 10, 0, 4, None, None) == 1
-    assert lib.tr_probe_mfma(ok_ptr, 16383, sink, 10, 0, 4, None, None) == 3
-    assert lib.tr_probe_mfma(ok_ptr + 2, 16384, sink, 10, 0, 4, None, None) == 4
-    assert lib.tr_probe_mfma(ok_ptr, 16384, sink, 0, 0, 4, None, None) == 3
-    assert lib.tr_probe_mfma(ok_ptr, 16384, sink, 10, 0, 0, None, None) == 3
-    assert lib.tr_probe_mfma(ok_ptr, 16384, sink, 10, 3, 4, None, None) == 6
-    assert b"tr_probe_mfma" in lib.tr_last_error()
+    B = ctypes.byref
+    q = _t(tr, tr.TR_BF16, 1, 4, 128, 128); k = _t(tr, tr.TR_BF16, 1, 4, 128, 128, ptr=0x7F1000000000)
+    v = _t(tr, tr.TR_BF16, 1, 4, 128, 128, ptr=0x7F2000000000)
+    o = _t(tr, tr.TR_F32, 1, 4, 128, 128, ptr=0x7F3000000000); l = _t(tr, tr.TR_F32, 1, 4, 128, 1, ptr=0x7F4000000000)
+    o_h0 = _t(tr, tr.TR_F32, 1, 4, 128, 128, ptr=0x7F3000000000, strides=(4 * 128 * 128, 0, 128))       # heads on top of each other
+    l_h0 = _t(tr, tr.TR_F32, 1, 4, 128, 1, ptr=0x7F4000000000, strides=(4 * 128, 0, 1))
+    o_short = _t(tr, tr.TR_F32, 1, 4, 128, 128, ptr=0x7F3000000000, strides=(4 * 128 * 128, 64 * 128, 128))  # head stride < S*D
+    for bad_o, bad_l in ((o_h0, l), (o, l_h0), (o_short, l)):
+        st, msg = _status(tr, lib.tr_block_attn, B(q), B(k), B(v), 0, 0.1, B(bad_o), B(bad_l), None)
+        assert st == 4 and "overlap itself" in msg
+        assert lib.tr_block_attn_merge(B(q), B(k), B(v), 0, 0.1, B(bad_o), B(bad_l), None) == 4
+        assert lib.tr_ring_attn(B(q), B(k), B(v), 2, 0, B(bad_o), B(bad_l), 0.0, None, 0, None) == 4
+        assert lib.tr_ring_attn_sched(B(q), B(k), B(v), 2, 0, 0, 1, B(bad_o), B(bad_l), 0.0, None) == 4
+    bo = _t(tr, tr.TR_F32, 1, 4, 128, 128, ptr=0x7F5000000000); bl = _t(tr, tr.TR_F32, 1, 4, 128, 1, ptr=0x7F6000000000)
+    assert lib.tr_merge(B(o_h0), B(l), B(bo), B(bl), None) == 4
+    assert lib.tr_merge(B(o), B(l_h0), B(bo), B(bl), None) == 4
+    P = ctypes.POINTER(tr.TrTensor)
+    assert lib.tr_merge_n(B(o_h0), B(l), (P * 1)(ctypes.pointer(bo)), (P * 1)(ctypes.pointer(bl)), 1, 0, None) == 4
+    # a token-major layout (the paper's (N, H, D)) is no overlap: stride_h = D, stride_s = H*D
+    o_tm = _t(tr, tr.TR_F32, 1, 4, 0, 128, ptr=0x7F3000000000, strides=(0, 128, 4 * 128))
+    l_tm = _t(tr, tr.TR_F32, 1, 4, 0, 1, ptr=0x7F4000000000, strides=(0, 1, 4))
+    q0 = _t(tr, tr.TR_BF16, 1, 4, 0, 128)
+    assert lib.tr_block_attn(B(q0), B(k), B(v), 0, 0.1, B(o_tm), B(l_tm), None) == 0      # Sq = 0: validated, nothing launched
+
+
+def test_bf16_partials_need_d_multiple_of_4_only(tr):
+    """tr_merge and tr_merge_n read bf16 partials four elements at a time: one rule for both (empty S: no launch)."""
+    lib = tr.raw_lib()
+    B = ctypes.byref
+    P = ctypes.POINTER(tr.TrTensor)
+    for D, ok in ((12, True), (20, True), (6, False), (10, False)):
+        ao = _t(tr, tr.TR_F32, 1, 2, 0, D); al = _t(tr, tr.TR_F32, 1, 2, 0, 1, ptr=0x7F1000000000)
+        bo = _t(tr, tr.TR_BF16, 1, 2, 0, D, ptr=0x7F2000000000); bl = _t(tr, tr.TR_F32, 1, 2, 0, 1, ptr=0x7F3000000000)
+        st_pair = lib.tr_merge(B(ao), B(al), B(bo), B(bl), None)
+        st_n = lib.tr_merge_n(B(ao), B(al), (P * 1)(ctypes.pointer(bo)), (P * 1)(ctypes.pointer(bl)), 1, 0, None)
+        assert (st_pair == 0) == ok and (st_n == 0) == ok, (D, st_pair, st_n)
+        assert st_pair == st_n
+
+
+def test_library_is_rebuilt_when_a_source_changes(tr, tmp_path, monkeypatch):
+    """The library carries the hash of its sources; ensure_built() compares it with the sources on disk."""
+    import shutil
+    from paper_2412_20501_amd import build
+    assert build.library_hash() == build.source_hash()
+    assert build.source_hash() in tr.tr_version()
+    # the same check against a copy of the sources with one byte changed: the hashes differ, so a build is due
+    csrc = tmp_path / "csrc"
+    shutil.copytree(build.CSRC, csrc)
+    with open(csrc / "merge.hip", "a") as f:
+        f.write("// touched\n")
+    monkeypatch.setattr(build, "CSRC", str(csrc))
+    assert build.source_hash() != build.library_hash()
+    calls = []
+    monkeypatch.setattr(build, "build_library", lambda verbose=False: calls.append(1) or build.LIB_PATH)
+    build.ensure_built()
+    assert calls == [1]
 
 
 def test_header_and_library_work_from_plain_c(tr, tmp_path):

@@ -58,6 +58,47 @@ def test_non_square_block_matches_mpmath():
     assert np.max(np.abs(out[0, 0] - o_ref)) < 1e-13 and np.max(np.abs(lse[0, 0] - l_ref)) < 1e-13
 
 
+def _mp_attention_at(q, k, v, scale, q_pos, k_pos):
+    """50-digit brute force with explicit sequence positions: key c is visible to row r iff
+    k_pos[c] <= q_pos[r] (Sec. 3.3.2).  A row that sees no key is the empty sum: out = 0, lse = -inf."""
+    mp.mp.dps = 50
+    out = np.zeros((len(q_pos), v.shape[1]))
+    lse = np.full(len(q_pos), -np.inf)
+    for r, qp in enumerate(q_pos):
+        keys = [c for c, kp in enumerate(k_pos) if kp <= qp]
+        if not keys:
+            continue
+        s = [mp.mpf(scale) * sum(mp.mpf(float(q[r, d])) * mp.mpf(float(k[c, d])) for d in range(q.shape[1])) for c in keys]
+        z = sum(mp.e ** x for x in s)
+        lse[r] = float(mp.log(z))
+        for d in range(v.shape[1]):
+            out[r, d] = float(sum((mp.e ** x) / z * mp.mpf(float(v[c, d])) for x, c in zip(s, keys)))
+    return out, lse
+
+
+@pytest.mark.parametrize("q_offset,k_offset,Sq,Sk", [(0, 3, 8, 8), (2, 5, 8, 6), (5, 2, 7, 8), (0, 8, 4, 4), (4, 0, 3, 9)])
+def test_causal_block_at_offsets_matches_mpmath(q_offset, k_offset, Sq, Sk):
+    """The causal rule at arbitrary chunk positions, as the zigzag partition of Sec. 3.3.2 needs it:
+    K/V chunks that start after the Query chunk leave early rows with few keys or none."""
+    D = 3
+    q, k, v = _rand((1, 1, Sq, D), 40 + q_offset), _rand((1, 1, Sk, D), 50 + k_offset), _rand((1, 1, Sk, D), 60)
+    out, lse = oracle.attention_block(q, k, v, 0.8, causal_diag=True, q_offset=q_offset, k_offset=k_offset)
+    o_ref, l_ref = _mp_attention_at(q[0, 0], k[0, 0], v[0, 0], 0.8, q_offset + np.arange(Sq), k_offset + np.arange(Sk))
+    empty = np.isneginf(l_ref)
+    # rows without a visible key: exactly the identity element of the Update
+    n_empty = sum(1 for r in range(Sq) if q_offset + r < k_offset)
+    assert empty.sum() == n_empty
+    assert np.all(np.isneginf(lse[0, 0][empty])) and np.all(out[0, 0][empty] == 0.0)
+    assert np.max(np.abs(out[0, 0] - o_ref)) < 1e-13
+    assert np.max(np.abs(lse[0, 0][~empty] - l_ref[~empty]), initial=0.0) < 1e-13
+    # number of visible keys per row, counted by hand: clamp(q_offset + r - k_offset + 1, 0, Sk)
+    zq = np.zeros_like(q)
+    _, lse0 = oracle.attention_block(zq, k, v, 0.8, causal_diag=True, q_offset=q_offset, k_offset=k_offset)
+    count = np.clip(q_offset + np.arange(Sq) - k_offset + 1, 0, Sk)
+    with np.errstate(divide="ignore"):
+        assert np.allclose(lse0[0, 0], np.log(count), atol=1e-14)
+
+
 # ---------------------------------------------------------------- library special cases
 @pytest.mark.parametrize("causal", [False, True])
 def test_attention_matches_torch_sdpa_fp64(causal):
