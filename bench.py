@@ -294,6 +294,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-extras", action="store_true", help="skip the merge-only and ring workloads")
+    ap.add_argument("--extras", default="", help="comma-separated names of the extras to run (default: all of them)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (untimed) so that HBM-traffic counters of a "
@@ -343,20 +344,26 @@ def main():
     }
     if not args.no_extras:
         ex_steps = max(3, min(args.steps, 10))
-        line["extras"] = {
-            "library_gemm_ceiling": bench_gemm_ceiling(),
-            "step_fused": bench_step_fused(tr, wl, ex_steps, 2),
-            "block_diag": bench_block_diag(tr, wl, ex_steps, 2),
-            "merge_only": bench_merge_only(tr, wl, 3, 1),
-            "ring_cfg1": bench_ring_small(tr, wl),
-            "ring_cfg3": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True),
-            "ring_cfg3_two_kernel": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=False),
-            "ring_cfg3_two_kernel_bf16_blocks": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=False, block_dtype=tr.TR_BF16),
-            "ring_cfg3_zigzag": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True, schedule=tr.TR_SCHED_ZIGZAG),
-            "ring_cfg3_hybrid_2x4": bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True, schedule=tr.TR_SCHED_HYBRID, n_inner=4),
-            "ring_cfg5": bench_ring(tr, wl, "cfg5_gqa", 2, 1, fused=True),
-            "ring_dit": bench_ring(tr, wl, "dit_ring", ex_steps, 1, fused=True),
+        table = {
+            "library_gemm_ceiling": lambda: bench_gemm_ceiling(),
+            "step_fused": lambda: bench_step_fused(tr, wl, ex_steps, 2),
+            "block_diag": lambda: bench_block_diag(tr, wl, ex_steps, 2),
+            "merge_only": lambda: bench_merge_only(tr, wl, 3, 1),
+            "ring_cfg1": lambda: bench_ring_small(tr, wl),
+            "ring_cfg3": lambda: bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True),
+            "ring_cfg3_two_kernel": lambda: bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=False),
+            "ring_cfg3_two_kernel_bf16_blocks": lambda: bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=False, block_dtype=tr.TR_BF16),
+            "ring_cfg3_zigzag": lambda: bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True, schedule=tr.TR_SCHED_ZIGZAG),
+            "ring_cfg3_hybrid_2x4": lambda: bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True, schedule=tr.TR_SCHED_HYBRID, n_inner=4),
+            "ring_cfg5": lambda: bench_ring(tr, wl, "cfg5_gqa", 2, 1, fused=True),
+            "ring_dit": lambda: bench_ring(tr, wl, "dit_ring", ex_steps, 1, fused=True),
         }
+        chosen = [n for n in args.extras.split(",") if n] or list(table)
+        unknown = [n for n in chosen if n not in table]
+        if unknown:
+            print(f"bench.py: unknown extras {unknown}; known: {list(table)}", file=sys.stderr)
+            sys.exit(2)
+        line["extras"] = {n: table[n]() for n in chosen}
         torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl)

@@ -223,10 +223,14 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   // Issued as inline asm: the compiler would otherwise treat every later LDS read as possibly
   // aliasing the in-flight load and drain vmcnt to 0 in front of it, serialising the pipeline;
   // here completion is waited for explicitly, one tile ahead of the first use.
+  // The statement overwrites m0.  The compiler reserves m0 and sets it itself right before each of
+  // its own uses (dynamic register indexing, LDS-direct forms), none of which this kernel
+  // contains: every register-array index is a compile-time constant.  (m0 cannot be named in
+  // the clobber list: it is a reserved register and the compiler rejects the promise.)
   const unsigned lds_base = (unsigned)(unsigned long)(lptr_t)lds;
   auto dma16 = [&](const __bf16* base, unsigned off, unsigned lds_off) __attribute__((always_inline)) {
     const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + lds_off);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(off), "s"(base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(off), "s"(base) : "memory");
   };
   // Tiles are issued strictly in order, so the tile base is a running wave-uniform pointer that
   // stops advancing at the last tile (later issues re-read it with the clamped offsets).
