@@ -176,6 +176,25 @@ tr_status tr_ring_attn_blocks(const tr_tensor* q, const tr_tensor* k, const tr_t
                               int block_dtype, void* workspace, size_t workspace_bytes, void* hip_stream);
 size_t tr_ring_attn_blocks_workspace_bytes(const tr_tensor* q, int n_chunks, int block_dtype);
 
+/*
+ * tr_ring_attn in its two-kernel form for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The block result that
+ * travels from tr_block_attn to tr_merge (fp32 block_out + block_lse of one step) lives in a
+ * device array inside the library (TR_NOALLOC_SCRATCH_BYTES, held by every GPU the library runs on
+ * until the process ends) instead of a caller workspace; the call allocates and frees nothing on
+ * the device and calls no allocating library routine.  Limit: one block result,
+ *   align256(B * Hq * (S / n_chunks) * D * 4) + align256(B * Hq * (S / n_chunks) * 4) bytes,
+ * must fit the array; larger problems return TR_ERR_WORKSPACE (use tr_ring_attn with a workspace).
+ * Arguments, checks, arithmetic and results are those of tr_ring_attn with a workspace (bitwise).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams or threads) race and must be serialised by the caller.  Nothing in the array needs
+ * clearing: every step overwrites the block result before the Update reads it.
+ */
+#define TR_NOALLOC_SCRATCH_BYTES (8 * 1024 * 1024 + 64 * 1024)
+tr_status tr_ring_attn_noalloc(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v,
+                               int n_chunks, int causal,
+                               const tr_tensor* out, const tr_tensor* lse, float scale, void* hip_stream);
+
 /* Order in which tr_ring_attn_sched runs the block steps (all "devices" replayed on one GPU). */
 typedef enum {
   TR_SCHED_TOKENRING = 0,      /* Algorithm 1: Q circulates, device j keeps K_j, V_j              */

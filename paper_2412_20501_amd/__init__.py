@@ -8,7 +8,7 @@ _EXPORTS = (
     "LIB_PATH", "TR_BF16", "TR_F32", "TR_MASK_CAUSAL_DIAG", "TR_MASK_NONE",
     "TR_SCHED_HYBRID", "TR_SCHED_RING_ATTENTION", "TR_SCHED_TOKENRING", "TR_SCHED_ZIGZAG", "TokenRingError", "TrTensor",
     "desc", "raw_lib", "tr_block_attn", "tr_block_attn_causal_at", "tr_block_attn_merge", "tr_merge", "tr_merge_n", "tr_ring_attn",
-    "tr_ring_attn_blocks", "tr_ring_attn_blocks_workspace_bytes", "tr_ring_attn_sched", "tr_ring_attn_workspace_bytes", "tr_schedule_steps", "tr_time_next_kernel", "tr_version",
+    "tr_ring_attn_blocks", "tr_ring_attn_noalloc", "tr_ring_attn_blocks_workspace_bytes", "tr_ring_attn_sched", "tr_ring_attn_workspace_bytes", "tr_schedule_steps", "tr_time_next_kernel", "tr_version",
 )
 __all__ = list(_EXPORTS)
 

@@ -57,6 +57,8 @@ def _load():
     lib.tr_ring_attn.argtypes = [P, P, P, ctypes.c_int, ctypes.c_int, P, P, ctypes.c_float,
                                  ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.tr_ring_attn.restype = ctypes.c_int
+    lib.tr_ring_attn_noalloc.argtypes = [P, P, P, ctypes.c_int, ctypes.c_int, P, P, ctypes.c_float, ctypes.c_void_p]
+    lib.tr_ring_attn_noalloc.restype = ctypes.c_int
     lib.tr_time_next_kernel.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
     lib.tr_time_next_kernel.restype = ctypes.c_int
     lib.tr_merge_n.argtypes = [P, P, ctypes.POINTER(P), ctypes.POINTER(P), ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
@@ -218,3 +220,9 @@ def tr_ring_attn(q, k, v, n_chunks, causal, out, lse, scale=0.0, workspace=None,
         ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     _check(_lib.tr_ring_attn(desc(q), desc(k), desc(v), int(n_chunks), int(bool(causal)), desc(out), desc(lse),
                              float(scale), ws_ptr, ws_bytes, _stream(stream)))
+
+
+def tr_ring_attn_noalloc(q, k, v, n_chunks, causal, out, lse, scale=0.0, stream=None):
+    """tr_ring_attn (two-kernel form) with the block workspace inside the library: nothing is allocated (see tokenring.h)."""
+    _check(_lib.tr_ring_attn_noalloc(desc(q), desc(k), desc(v), int(n_chunks), int(bool(causal)), desc(out), desc(lse),
+                                     float(scale), _stream(stream)))

@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
 #include <vector>
 
 #include "tr_internal.h"
@@ -275,6 +276,30 @@ tr_status run_steps_fused(const tr_tensor* q, const tr_tensor* k, const tr_tenso
 constexpr size_t kWsAlign = 256;
 size_t align_up(size_t x) { return (x + kWsAlign - 1) / kWsAlign * kWsAlign; }
 
+// Block workspace of tr_ring_attn_noalloc: one block result (block_out + block_lse) of the
+// two-kernel form, held in a device array of the library itself so that the call needs no
+// allocation.  Every GPU the library runs on holds its own copy until the process ends.  In
+// host code the array's name is only a handle: the device address is resolved once per device
+// (with that device current) and kept in g_scratch_ptr; kernels only ever see that address.
+__device__ __align__(256) static unsigned char scratch[TR_NOALLOC_SCRATCH_BYTES];
+constexpr int kScratchMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kScratchMaxDevices];
+
+tr_status scratch_of_current_device(void** ptr_out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(TR_ERR_HIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kScratchMaxDevices) return fail(TR_ERR_UNSUPPORTED, "device index %d beyond the %d devices supported", dev, kScratchMaxDevices);
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return fail(TR_ERR_HIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // the same address from any thread that races here
+  }
+  *ptr_out = ptr;
+  return TR_OK;
+}
+
 }  // namespace
 
 namespace tr {
@@ -534,6 +559,22 @@ tr_status tr_ring_attn_blocks(const tr_tensor* q, const tr_tensor* k, const tr_t
   if (block_dtype != TR_F32 && block_dtype != TR_BF16) return fail(TR_ERR_DTYPE, "block_dtype %d is neither fp32 nor bf16", block_dtype);
   if (!workspace) return fail(TR_ERR_WORKSPACE, "the two-kernel form needs a workspace");
   return ring_attn_impl(q, k, v, n_chunks, causal, out, lse, scale, block_dtype, workspace, workspace_bytes, hip_stream);
+}
+
+tr_status tr_ring_attn_noalloc(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int n_chunks, int causal,
+                               const tr_tensor* out, const tr_tensor* lse, float scale, void* hip_stream) {
+  g_err[0] = 0;
+  // size check first (needs no device): the block result of one step must fit the library's array
+  const size_t need = tr_ring_attn_blocks_workspace_bytes(q, n_chunks, TR_F32);
+  if (q && n_chunks >= 1 && q->S >= 0 && q->S % n_chunks == 0 && need > (size_t)TR_NOALLOC_SCRATCH_BYTES)
+    return fail(TR_ERR_WORKSPACE, "tr_ring_attn_noalloc: one block result needs %zu bytes, the built-in scratch holds %zu "
+                "(B * Hq * (S / n_chunks) * (D + 1) * 4 bytes must fit); use tr_ring_attn with a workspace", need,
+                (size_t)TR_NOALLOC_SCRATCH_BYTES);
+  if (!q || !k || !v || !out || !lse) return fail(TR_ERR_NULL, "a tensor descriptor is NULL");
+  void* ws = nullptr;
+  const tr_status st = scratch_of_current_device(&ws);
+  if (st != TR_OK) return st;
+  return ring_attn_impl(q, k, v, n_chunks, causal, out, lse, scale, TR_F32, ws, (size_t)TR_NOALLOC_SCRATCH_BYTES, hip_stream);
 }
 
 int64_t tr_schedule_steps(int schedule, int n_devices, int n_inner, int causal, int32_t* steps_out, int64_t capacity) {

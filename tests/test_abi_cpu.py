@@ -27,7 +27,7 @@ def _t(tr, dtype, B, H, S, D, ptr=0x7F0000000000, strides=None):
 def test_every_declared_symbol_is_exported(tr):
     text = open(HEADER).read()
     names = set(re.findall(r"\b(tr_[a-z_]+)\s*\(", text))
-    assert {"tr_block_attn", "tr_block_attn_causal_at", "tr_block_attn_merge", "tr_merge", "tr_merge_n", "tr_ring_attn", "tr_ring_attn_blocks", "tr_ring_attn_blocks_workspace_bytes", "tr_ring_attn_sched", "tr_schedule_steps",
+    assert {"tr_block_attn", "tr_block_attn_causal_at", "tr_block_attn_merge", "tr_merge", "tr_merge_n", "tr_ring_attn", "tr_ring_attn_blocks", "tr_ring_attn_noalloc", "tr_ring_attn_blocks_workspace_bytes", "tr_ring_attn_sched", "tr_schedule_steps",
             "tr_ring_attn_workspace_bytes", "tr_time_next_kernel", "tr_last_error", "tr_version"} <= names
     lib = ctypes.CDLL(tr.LIB_PATH)
     for n in names:
@@ -202,6 +202,19 @@ def test_library_is_rebuilt_when_a_source_changes(tr, tmp_path, monkeypatch):
     monkeypatch.setattr(build, "build_library", lambda verbose=False: calls.append(1) or build.LIB_PATH)
     build.ensure_built()
     assert calls == [1]
+
+
+def test_noalloc_ring_rejects_oversize_before_touching_a_device(tr):
+    lib = tr.raw_lib()
+    B = ctypes.byref
+    q = _t(tr, tr.TR_BF16, 1, 32, 32768, 128); k = _t(tr, tr.TR_BF16, 1, 32, 32768, 128, ptr=0x7F1000000000)
+    v = _t(tr, tr.TR_BF16, 1, 32, 32768, 128, ptr=0x7F2000000000)
+    o = _t(tr, tr.TR_F32, 1, 32, 32768, 128, ptr=0x7F3000000000); l = _t(tr, tr.TR_F32, 1, 32, 32768, 1, ptr=0x7F5000000000)
+    st, msg = _status(tr, lib.tr_ring_attn_noalloc, B(q), B(k), B(v), 8, 1, B(o), B(l), 0.0, None)
+    assert st == 7 and "scratch" in msg and "workspace" in msg
+    assert lib.tr_ring_attn_noalloc(None, B(k), B(v), 8, 1, B(o), B(l), 0.0, None) == 1
+    text = open(HEADER).read()
+    assert "#define TR_NOALLOC_SCRATCH_BYTES (8 * 1024 * 1024 + 64 * 1024)" in text
 
 
 def test_header_and_library_work_from_plain_c(tr, tmp_path):
