@@ -279,9 +279,11 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   for (int db = 0; db < DB; db++)
 #pragma unroll
     for (int i = 0; i < 16; i++) o_acc[db][i] = 0.f;
+  constexpr float kSumCap = 65536.f;
   float m_ref = -INFINITY;  // exponent reference of this query, in raw (unscaled) score units
   float mc = 0.f;           // m_ref * c2 (0 while m_ref is -inf), kept alongside m_ref
   float l_run = 0.f;        // this lane's share of the running sum of exp
+  float sum_cap = -1.f;     // largest sub-tile sum the fast path accepts; negative until m_ref is finite
   const float c2 = p.scale * 1.4426950408889634f;  // scale * log2(e)
 
   // ---- one step ---------------------------------------------------------------------
@@ -323,16 +325,16 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   };
   bf16x8 pre[NQK];  // K operands of the next step's QK half, read one step ahead
 
-  constexpr float kSumCap = 65536.f;
   auto step = [&](int kstart, auto first_c, auto v_imm_c, auto k_imm_next_c, f32x16& s_in, f32x16& s_out,
-                  bf16x8 (&p_in)[2], bf16x8 (&p_out)[2]) __attribute__((always_inline)) {
+                  bf16x8 (&p_in)[2], bf16x8 (&p_out)[2], auto inner_c) __attribute__((always_inline)) {
     constexpr bool FIRST = decltype(first_c)::value != 0;   // no previous sub-tile: QK half only
+    constexpr bool INNER = decltype(inner_c)::value != 0;   // every key of the sub-tile is visible to every row: no mask test
     constexpr int n_mfma = FIRST ? NQK : NQK + NPV;
     constexpr int EPM = 16 / n_mfma;  // softmax elements handled per MFMA slice
     static_assert(16 % n_mfma == 0, "softmax elements must divide evenly over the MFMAs");
     constexpr unsigned v_imm = decltype(v_imm_c)::value, k_imm_next = decltype(k_imm_next_c)::value;
 
-    if (kstart > kmask_from) {  // some key of the sub-tile is past Sk or above this wave's first diagonal
+    if (!INNER && kstart > kmask_from) {  // some key of the sub-tile is past Sk or above this wave's first diagonal
       int limit = p.Sk - 1;
       if (causal) limit = min(limit, qrow + p.causal_off);
 #pragma unroll
@@ -400,7 +402,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     for (int h = 0; h < 2; h++) p_out[h] = __builtin_bit_cast(bf16x8, u32x4{pw[4 * h], pw[4 * h + 1], pw[4 * h + 2], pw[4 * h + 3]});
     float psum = ps0 + ps1;
 
-    if (__any(!(psum <= kSumCap) || m_ref == -INFINITY)) {
+    if (__any(!(psum <= sum_cap))) {   // sum_cap < 0 while m_ref is -inf, so that case is included
       float tmax = s_in[0];
 #pragma unroll
       for (int i = 1; i < 16; i++) tmax = fmaxf(tmax, s_in[i]);
@@ -415,6 +417,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
         for (int i = 0; i < 16; i++) o_acc[db][i] *= a;
       m_ref = m_new;
       mc = (m_ref == -INFINITY) ? 0.f : m_ref * c2;
+      sum_cap = (m_ref == -INFINITY) ? -1.f : kSumCap;
       const float mc2 = mc;
       float q0s = 0.f, q1s = 0.f;
 #pragma unroll
@@ -432,6 +435,21 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     s_out = acc;
 #pragma unroll
     for (int i = 0; i < NQK; i++) pre[i] = nxt[i];
+  };
+
+  // Tiles that are certain to lie before the last tile of the K/V segment need neither the choice
+  // between the two offset sets nor the end-of-stream test.
+  auto issue_k_inner = [&](int slot) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < IPW; i++) dma16(k_next, k_off[i], slot * TILE_BYTES + (wave * IPW + i) * 1024);
+    k_next = uniform_ptr(k_next + k_tile_stride);
+    k_left--;
+  };
+  auto issue_v_inner = [&](int slot) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < IPW; i++) dma16(v_next, v_off[i], (NS + slot) * TILE_BYTES + (wave * IPW + i) * 1024);
+    v_next = uniform_ptr(v_next + v_tile_stride);
+    v_left--;
   };
 
   // ---- prologue: K_0..K_2, V_0, V_1 into the rings
@@ -460,15 +478,16 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   bf16x8 pA[2], pB[2];
   constexpr unsigned SUBB = SUB * RB;  // bytes of one sub-tile inside a tile
   // Step NSUB*u + kt of the tile in ring slot `su` (previous tile in sp, next in sn).
-  auto tile_step = [&](int u, auto su_c, auto kt_c) __attribute__((always_inline)) {
+  auto tile_step = [&](int u, auto su_c, auto kt_c, auto inner_c) __attribute__((always_inline)) {
     constexpr int su = decltype(su_c)::value, kt = decltype(kt_c)::value;
+    constexpr bool INNER = decltype(inner_c)::value != 0;   // the step certainly runs and needs no mask
     constexpr int sp = (su + NS - 1) % NS, sn = (su + 1) % NS;
     constexpr unsigned v_imm = kt == 0 ? sp * TILE_BYTES + (NSUB - 1) * SUBB : su * TILE_BYTES + (kt - 1) * SUBB;
     constexpr unsigned k_imm = kt + 2 < NSUB ? su * TILE_BYTES + (kt + 2) * SUBB : sn * TILE_BYTES + (kt + 2 - NSUB) * SUBB;
     const int j = NSUB * u + kt;
-    if (j <= (kt == 0 ? jw_first : jw_in)) {
-      if (kt % 2 == 0) step(j * SUB, IC<0>{}, IC<(int)v_imm>{}, IC<(int)k_imm>{}, sA, sB, pB, pA);
-      else step(j * SUB, IC<0>{}, IC<(int)v_imm>{}, IC<(int)k_imm>{}, sB, sA, pA, pB);
+    if (INNER || j <= (kt == 0 ? jw_first : jw_in)) {
+      if (kt % 2 == 0) step(j * SUB, IC<0>{}, IC<(int)v_imm>{}, IC<(int)k_imm>{}, sA, sB, pB, pA, inner_c);
+      else step(j * SUB, IC<0>{}, IC<(int)v_imm>{}, IC<(int)k_imm>{}, sB, sA, pA, pB, inner_c);
     }
   };
   if (n_tiles > 0) {
@@ -484,36 +503,61 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
       for (int ks = 0; ks < KS; ks++) pre[ks] = load_k(ks, SUBB);
       // step 0: S_1 alongside the softmax of sub-tile 0 (no PV yet); prefetch the K operands of sub-tile 2
       constexpr unsigned k_imm0 = 2 < NSUB ? 2 * SUBB : 1 * TILE_BYTES;
-      step(0, IC<1>{}, IC<0>{}, IC<(int)k_imm0>{}, sA, sB, pB, pA);
+      step(0, IC<1>{}, IC<0>{}, IC<(int)k_imm0>{}, sA, sB, pB, pA, IC<0>{});
       // the other steps of tile 0 (tiles 0 and 1 sit in ring slots 0 and 1)
-      tile_step(0, IC<0>{}, IC<1>{});
+      tile_step(0, IC<0>{}, IC<1>{}, IC<0>{});
       if constexpr (NSUB > 2) {
-        tile_step(0, IC<0>{}, IC<2>{});
-        tile_step(0, IC<0>{}, IC<3>{});
+        tile_step(0, IC<0>{}, IC<2>{}, IC<0>{});
+        tile_step(0, IC<0>{}, IC<3>{}, IC<0>{});
       }
     }
   }
   // tiles u = 1 .. n_tiles: steps NSUB*u .. NSUB*u + NSUB-1 (the last tile index only has its first
   // step, which folds in the PV product of the final sub-tile; its softmax sees only masked keys)
-  auto tile_body = [&](int u, auto slot_c) __attribute__((always_inline)) {   // slot_c = u % NS
+  auto tile_body = [&](int u, auto slot_c, auto inner_c) __attribute__((always_inline)) {   // slot_c = u % NS
     constexpr int su = decltype(slot_c)::value;
+    constexpr bool INNER = decltype(inner_c)::value != 0;
     __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * IPW));  // vmcnt only
     wg_barrier();                                    // B_u
-    issue_k((su + 3) % NS);   // K_{u+3}
-    issue_v((su + 2) % NS);   // V_{u+2}
-    tile_step(u, slot_c, IC<0>{});
-    tile_step(u, slot_c, IC<1>{});
+    if (INNER) {
+      issue_k_inner((su + 3) % NS);   // K_{u+3}
+      issue_v_inner((su + 2) % NS);   // V_{u+2}
+    } else {
+      issue_k((su + 3) % NS);
+      issue_v((su + 2) % NS);
+    }
+    tile_step(u, slot_c, IC<0>{}, inner_c);
+    tile_step(u, slot_c, IC<1>{}, inner_c);
     if constexpr (NSUB > 2) {
-      tile_step(u, slot_c, IC<2>{});
-      tile_step(u, slot_c, IC<3>{});
+      tile_step(u, slot_c, IC<2>{}, inner_c);
+      tile_step(u, slot_c, IC<3>{}, inner_c);
     }
   };
   static_assert(NSUB == 2 || NSUB == 4, "tile_body spells out 2 or 4 steps");
-  for (int u0 = 0; u0 <= n_tiles; u0 += NS) {
-    if (u0 >= 1) tile_body(u0, IC<0>{});
-    if (u0 + 1 <= n_tiles) tile_body(u0 + 1, IC<1 % NS>{});
-    if (u0 + 2 <= n_tiles) tile_body(u0 + 2, IC<2 % NS>{});
-    if (u0 + 3 <= n_tiles) tile_body(u0 + 3, IC<3 % NS>{});
+  // Inner tiles: every step of the tile runs in this wave without masking (all its keys are visible
+  // to all of the wave's rows and lie inside the K/V segment) and the tiles it puts on their way
+  // lie before the segment's last tile.  They take a tile body without the per-step tests; the
+  // remaining tiles take the general one.  Both bodies hold the same barrier and the same number
+  // of loads, so the waves of a workgroup may disagree about where the inner tiles end.
+  const int j_inner = min(jw_in, kmask_from >= 0 ? kmask_from / SUB : -1) - (NSUB - 1);   // last step of the tile must pass both tests
+  int u_inner = j_inner < 0 ? -1 : j_inner / NSUB;
+  u_inner = __builtin_amdgcn_readfirstlane(min(u_inner, last_tile - 4));   // loads issued in tile u reach tile u + 3
+  // tiles 1 .. 3 (tile 0 was the prologue)
+  if (1 <= n_tiles) tile_body(1, IC<1 % NS>{}, IC<0>{});
+  if (2 <= n_tiles) tile_body(2, IC<2 % NS>{}, IC<0>{});
+  if (3 <= n_tiles) tile_body(3, IC<3 % NS>{}, IC<0>{});
+  int u0 = NS;
+  for (; u0 + NS - 1 <= u_inner; u0 += NS) {
+    tile_body(u0, IC<0>{}, IC<1>{});
+    tile_body(u0 + 1, IC<1 % NS>{}, IC<1>{});
+    tile_body(u0 + 2, IC<2 % NS>{}, IC<1>{});
+    tile_body(u0 + 3, IC<3 % NS>{}, IC<1>{});
+  }
+  for (; u0 <= n_tiles; u0 += NS) {
+    tile_body(u0, IC<0>{}, IC<0>{});
+    if (u0 + 1 <= n_tiles) tile_body(u0 + 1, IC<1 % NS>{}, IC<0>{});
+    if (u0 + 2 <= n_tiles) tile_body(u0 + 2, IC<2 % NS>{}, IC<0>{});
+    if (u0 + 3 <= n_tiles) tile_body(u0 + 3, IC<3 % NS>{}, IC<0>{});
   }
   __builtin_amdgcn_s_waitcnt(0);  // no LDS write of this workgroup may still be in flight at exit
 
