@@ -6,10 +6,18 @@ One JSON line on stdout.  A *step* is one iteration of Algorithm 1 on one device
 followed by tr_merge of that block into the fp32 accumulators.  `value` is the step's
 attention TFLOP (4*Sq*Sk*D per head) divided by the whole step time, inputs resident in
 HBM.  `roofline` is the block-attention kernel against the bf16 MFMA peak, from HIP-event
-durations recorded around every launch of the timed region; `merge_roofline` is the same
-for the merge kernel against HBM.  `extras` adds the library GEMM's rate on this machine, the fused
-step, the merge-only bandwidth workload (pairwise and n-ary) and the ring-schedule workloads.  `cpu_baseline` times the fp64 oracle on a few heads of the
-same block step on the host cores.
+durations carried by every launch of the timed region; `merge_roofline` is the same for the
+merge kernel against HBM.  `parity` holds the max-abs errors of the same step against the
+fp64 oracle on four heads.  `extras` adds the library GEMM's rate on this machine, the fused
+step, the block step on other score distributions, the merge-only bandwidth workload
+(pairwise and n-ary), the ring-schedule workloads and oracle timings of the other
+workloads.  `cpu_baseline` times the fp64 oracle on heads of the same block step on the
+host cores.
+
+Before the warm-up steps the step runs untimed for about half a second: an idle MI355X needs
+a few hundred milliseconds of load to leave its low-power clock state (rocm-smi shows the
+shader clock climbing over that time), and a ring schedule keeps the device busy for far
+longer than that, so the sustained state is the one to measure.  --no-ramp skips it.
 """
 import argparse
 import json
@@ -23,11 +31,23 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
-# HBM bytes per launch of the two kernels of the cfg2 step, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# summarised in profiles/block_step_cfg2_block_attn_and_merge.md (KiB per dispatch; FETCH_SIZE scaled by the 2.0 that a
-# plain 1 GiB copy calibrates, WRITE_SIZE by 1.0).  Counters cannot be read from inside this process.
-TRAFFIC_ATTN_BYTES = (82123 * 2 + 33280) * 1024
-TRAFFIC_MERGE_BYTES = (51230 * 2 + 66048) * 1024
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
+
+
+def _traffic(kernel):
+    """HBM bytes per launch of a kernel of the cfg2 step, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs that
+    profiles/traffic.json records (counters cannot be read from inside this process); None if not recorded."""
+    try:
+        with open(TRAFFIC_JSON) as f:
+            return int(json.load(f)[kernel]["hbm_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
+def _median(xs):
+    xs = sorted(xs)
+    n = len(xs)
+    return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
 
 
 def _dev(bits):
@@ -40,7 +60,8 @@ def _event_ms(pairs):
     return [a.elapsed_time(b) for a, b in pairs]
 
 
-def bench_block_step(tr, wl, steps, warmup):
+def bench_block_step(tr, wl, steps, warmup, ramp_s):
+    import numpy as np
     import torch
     cfg = wl.CONFIGS["cfg2_block"]
     qb, kb, vb = wl.make_qkv_bits(cfg)
@@ -63,6 +84,29 @@ def bench_block_step(tr, wl, steps, warmup):
             tr.tr_time_next_kernel(ev[2], ev[3])
         tr.tr_merge(acc_o, acc_l, blk_o, blk_l, stream)
 
+    # parity of exactly this step (first one: the accumulators start as the identity of the Update) on four heads
+    import oracle
+    step()
+    torch.cuda.synchronize()
+    heads = [0, 13, 22, 31]
+    err = {"block_out": 0.0, "block_lse": 0.0, "acc_out": 0.0, "acc_lse": 0.0}
+    f = wl.bf16_bits_to_f64
+    for h in heads:
+        ref_o, ref_l = oracle.attention_block(f(qb[:, h:h + 1]), f(kb[:, h:h + 1]), f(vb[:, h:h + 1]), cfg.scale)
+        d = lambda t, ref: float(np.max(np.abs(t.float().cpu().numpy().astype(np.float64) - ref)))
+        err["block_out"] = max(err["block_out"], d(blk_o[:, h:h + 1], ref_o))
+        err["block_lse"] = max(err["block_lse"], d(blk_l[:, h:h + 1], ref_l))
+        err["acc_out"] = max(err["acc_out"], d(acc_o[:, h:h + 1], ref_o))      # Update of the identity with the block
+        err["acc_lse"] = max(err["acc_lse"], d(acc_l[:, h:h + 1], ref_l))
+    parity = {"against": "fp64 oracle, heads %s of the timed step in full" % heads, "max_abs": err,
+              "tolerance": {"out": 1e-2, "lse": 1e-3}, "ok": bool(max(err["block_out"], err["acc_out"]) <= 1e-2 and
+                                                                max(err["block_lse"], err["acc_lse"]) <= 1e-3)}
+
+    t_ramp = time.perf_counter()
+    while time.perf_counter() - t_ramp < ramp_s:      # untimed: lets the device reach its sustained clock state
+        for _ in range(50):
+            step()
+        torch.cuda.synchronize()
     for _ in range(warmup):
         step()
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
@@ -82,8 +126,9 @@ def bench_block_step(tr, wl, steps, warmup):
     flops = 4.0 * S * S * D * H * B                              # algorithmic: 4*D per (q,k) pair
     merge_bytes = B * H * S * (D * (4 + 2 + 4) + 3 * 4)          # read acc fp32 + block bf16, write acc; 3 lse words
     return {
-        "cfg": cfg, "ms_per_step": ms_per_step, "flops": flops,
-        "attn_ms_avg": attn_avg, "attn_ms_min": min(attn_ms), "merge_ms_avg": merge_avg,
+        "cfg": cfg, "ms_per_step": ms_per_step, "flops": flops, "parity": parity,
+        "attn_ms_avg": attn_avg, "attn_ms_median": _median(attn_ms), "attn_ms_min": min(attn_ms),
+        "merge_ms_avg": merge_avg, "merge_ms_median": _median(merge_ms), "merge_ms_min": min(merge_ms),
         "attn_tflops": flops / (attn_avg * 1e-3) / 1e12,
         "merge_gbs": merge_bytes / (merge_avg * 1e-3) / 1e9, "merge_bytes": merge_bytes,
     }
@@ -161,23 +206,24 @@ def bench_step_fused(tr, wl, steps, warmup):
             "tflops": flops / (ms * 1e-3) / 1e12, "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
 
 
-def bench_block_diag(tr, wl, steps, warmup):
-    """The diagonal-causal variant of the block step (half the pairs)."""
+def bench_block(tr, wl, name, steps, warmup, what):
+    """One block step (bf16 block_out) of a named 4096 x 4096 workload: diagonal-causal, or another score distribution."""
     import torch
-    cfg = wl.CONFIGS["cfg2_block_diag"]
+    cfg = wl.CONFIGS[name]
     qb, kb, vb = wl.make_qkv_bits(cfg)
     q, k, v = _dev(qb), _dev(kb), _dev(vb)
     blk_o = torch.empty((cfg.B, cfg.Hq, cfg.S, cfg.D), dtype=torch.bfloat16, device="cuda")
     blk_l = torch.empty((cfg.B, cfg.Hq, cfg.S), dtype=torch.float32, device="cuda")
+    mask = tr.TR_MASK_CAUSAL_DIAG if cfg.causal else tr.TR_MASK_NONE
     for _ in range(warmup):
-        tr.tr_block_attn(q, k, v, tr.TR_MASK_CAUSAL_DIAG, cfg.scale, blk_o, blk_l)
+        tr.tr_block_attn(q, k, v, mask, cfg.scale, blk_o, blk_l)
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-    for a, b in ev:
-        a.record(); tr.tr_block_attn(q, k, v, tr.TR_MASK_CAUSAL_DIAG, cfg.scale, blk_o, blk_l); b.record()
+    for a_, b_ in ev:
+        tr.tr_time_next_kernel(a_, b_); tr.tr_block_attn(q, k, v, mask, cfg.scale, blk_o, blk_l)
     torch.cuda.synchronize()
-    ms = sum(_event_ms(ev)) / steps
-    flops = 2.0 * cfg.S * (cfg.S + 1) * cfg.D * cfg.Hq * cfg.B
-    return {"workload": "cfg2 diagonal-causal block step", "ms": ms, "tflops": flops / (ms * 1e-3) / 1e12,
+    ms = _median(_event_ms(ev))
+    flops = (2.0 * cfg.S * (cfg.S + 1) if cfg.causal else 4.0 * cfg.S * cfg.S) * cfg.D * cfg.Hq * cfg.B
+    return {"workload": what, "ms_median": ms, "tflops": flops / (ms * 1e-3) / 1e12,
             "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
 
 
@@ -264,14 +310,18 @@ def bench_ring(tr, wl, name, steps, warmup, fused, schedule=None, n_inner=1, blo
             "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
 
 
-def cpu_baseline(wl, budget_s=12.0):
-    """The fp64 oracle on heads of the same block step, on this box's host cores, for about budget_s seconds."""
-    import oracle
+def _blas_threads():
     try:
         from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] or [1]))
     except Exception:
-        threads = os.cpu_count() or 1
+        return int(os.cpu_count() or 1)
+
+
+def cpu_baseline(wl, budget_s=10.0):
+    """The fp64 oracle on heads of the same block step, on this box's host cores, for about budget_s seconds."""
+    import oracle
+    threads = _blas_threads()
     cfg = wl.CONFIGS["cfg2_block"]
     qb, kb, vb = wl.make_qkv_bits(cfg)
     f = wl.bf16_bits_to_f64
@@ -283,19 +333,62 @@ def cpu_baseline(wl, budget_s=12.0):
         t_used += time.perf_counter() - t0
         heads += 1
     flops = 4.0 * cfg.S * cfg.S * cfg.D * heads
-    return {"value": flops / t_used / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+    return {"value": flops / t_used / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
             "sample": f"{heads} head-passes (heads taken cyclically out of {cfg.Hq}) of the 4096x4096 D=128 block step, "
                       f"fp64 numpy, {t_used:.1f} s"}
+
+
+def oracle_timings(wl):
+    """The oracle on the other workloads, each on a bounded sample (a few seconds): the small ring workload in full,
+    a down-scaled merge-only workload, and sampled rows of one head of the two long causal rings, whose time for
+    the whole workload is extrapolated by the ratio of (query, key) pairs."""
+    import numpy as np
+    import oracle
+    f = wl.bf16_bits_to_f64
+    res = {"cores": _blas_threads()}
+    cfg = wl.CONFIGS["cfg1_small"]
+    qb, kb, vb = wl.make_qkv_bits(cfg)
+    t0 = time.perf_counter()
+    reps = 0
+    while reps == 0 or time.perf_counter() - t0 < 1.0:
+        oracle.ring_attention(f(qb), f(kb), f(vb), cfg.n_chunks, cfg.causal, cfg.scale)
+        reps += 1
+    res["cfg1_ring_full"] = {"ms": (time.perf_counter() - t0) * 1e3 / reps, "what": "Algorithm 1 replayed by the oracle, whole workload"}
+    mc = wl.CONFIGS["cfg4_merge"]
+    S4 = 1024
+    outs, lses = wl.make_merge_partials(mc, S=S4)
+    t0 = time.perf_counter()
+    oracle.merge_nary(outs, lses)
+    t = time.perf_counter() - t0
+    byts = 3 * mc.n_partials * mc.B * mc.H * S4 * (mc.D + 1) * 4      # what the eight pairwise Updates move
+    res["cfg4_merge_scaled"] = {"ms": t * 1e3, "gbs": byts / t / 1e9, "what": f"8 partials of [1,32,{S4},128] (1/32 of the workload), n-ary definition"}
+    for name in ("cfg3_ring", "cfg5_gqa"):
+        c = wl.CONFIGS[name]
+        rng = np.random.Generator(np.random.PCG64(c.seed + 7))
+        kh = rng.standard_normal((c.S, c.D)) * c.std          # one K/V head drawn like the workload (timing only)
+        vh = rng.standard_normal((c.S, c.D)) * c.std
+        rows = wl.sample_rows(c.S, c.chunk, 48, seed=c.seed + 1)
+        qh = rng.standard_normal((len(rows), c.D)) * c.std
+        t0 = time.perf_counter()
+        oracle.attention_rows(qh, rows, kh, vh, c.scale, True)
+        t = time.perf_counter() - t0
+        pairs = float(np.sum(rows + 1))
+        total_pairs = c.B * c.Hq * (c.S * (c.S + 1) / 2.0)
+        res[name + "_extrapolated"] = {"sample_ms": t * 1e3, "sample": f"{len(rows)} query rows of one head ({pairs:.3g} pairs)",
+                                       "tflops": 4.0 * c.D * pairs / t / 1e12,
+                                       "whole_workload_s_extrapolated": t * total_pairs / pairs}
+    return res
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-extras", action="store_true", help="skip the merge-only and ring workloads")
     ap.add_argument("--extras", default="", help="comma-separated names of the extras to run (default: all of them)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ramp", action="store_true", help="skip the untimed half second that brings the device out of its idle clock state")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (untimed) so that HBM-traffic counters of a "
                          "profiler run can be scaled by what they read for a copy of known size")
@@ -307,13 +400,14 @@ def main():
     import torch
 
     from paper_2412_20501_amd.build import ensure_built
-    ensure_built()              # compiles only if no library has been built yet
+    ensure_built()              # compiles unless the library on disk was built from exactly these sources
     import paper_2412_20501_amd as tr
     import workloads as wl
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     tr.raw_lib()   # fails loudly if libtokenring.so is missing
+    print(f"bench.py: {tr.tr_version()} on {torch.cuda.get_device_name(0)}", file=sys.stderr)
 
     if args.calibration_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -323,7 +417,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    r = bench_block_step(tr, wl, args.steps, args.warmup)
+    r = bench_block_step(tr, wl, args.steps, args.warmup, 0.0 if args.no_ramp else 0.6)
     cfg = r["cfg"]
     value = r["flops"] / (r["ms_per_step"] * 1e-3) / 1e12
     line = {
@@ -333,21 +427,28 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "cfg2 block step: B1 H32 Sq4096 x Sk4096 D128 bf16 N(0,1), non-causal, "
                                "bf16 block_out + fp32 block_lse merged into fp32 accumulators",
-                   "seed": cfg.seed, "scale": cfg.scale},
+                   "seed": cfg.seed, "scale": cfg.scale, "library": tr.tr_version(),
+                   "clock_ramp_s": 0.0 if args.no_ramp else 0.6},
         "roofline": {"bound": "mfma", "kernel": "block_attn_kernel<128,bf16 out>", "achieved": r["attn_tflops"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": r["attn_tflops"] / PEAK_BF16_TFLOPS,
-                     "traffic": TRAFFIC_ATTN_BYTES, "ms_avg": r["attn_ms_avg"], "ms_min": r["attn_ms_min"],
-                     "flops_per_launch": r["flops"]},
+                     "traffic": _traffic("block_attn_cfg2"), "ms_avg": r["attn_ms_avg"], "ms_median": r["attn_ms_median"],
+                     "ms_min": r["attn_ms_min"], "flops_per_launch": r["flops"]},
         "merge_roofline": {"bound": "hbm", "kernel": "merge_kernel<bf16 block>", "achieved": r["merge_gbs"],
                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": r["merge_gbs"] / PEAK_HBM_GBS,
-                           "traffic": TRAFFIC_MERGE_BYTES, "ms_avg": r["merge_ms_avg"], "bytes_per_launch": r["merge_bytes"]},
+                           "traffic": _traffic("merge_cfg2"), "ms_avg": r["merge_ms_avg"], "ms_median": r["merge_ms_median"],
+                           "ms_min": r["merge_ms_min"], "bytes_per_launch": r["merge_bytes"]},
+        "parity": r["parity"],
     }
     if not args.no_extras:
         ex_steps = max(3, min(args.steps, 10))
         table = {
             "library_gemm_ceiling": lambda: bench_gemm_ceiling(),
             "step_fused": lambda: bench_step_fused(tr, wl, ex_steps, 2),
-            "block_diag": lambda: bench_block_diag(tr, wl, ex_steps, 2),
+            "block_diag": lambda: bench_block(tr, wl, "cfg2_block_diag", ex_steps, 2, "cfg2 diagonal-causal block step"),
+            "block_wide_scores": lambda: bench_block(tr, wl, "cfg2_block_wide", ex_steps, 2,
+                                                     "cfg2 block step with Q, K ~ N(0, 3^2): scaled scores about 9 standard deviations wide"),
+            "block_ramp_scores": lambda: bench_block(tr, wl, "cfg2_block_ramp", ex_steps, 2,
+                                                     "cfg2 block step with scores rising 0.01 per key (+41 over the chunk)"),
             "merge_only": lambda: bench_merge_only(tr, wl, 3, 1),
             "ring_cfg1": lambda: bench_ring_small(tr, wl),
             "ring_cfg3": lambda: bench_ring(tr, wl, "cfg3_ring", ex_steps, 1, fused=True),
@@ -367,6 +468,8 @@ def main():
         torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl)
+        if not args.no_extras and not args.extras:
+            line["extras"]["oracle_timings"] = oracle_timings(wl)
     print(json.dumps(line))
 
 

@@ -279,7 +279,13 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   for (int db = 0; db < DB; db++)
 #pragma unroll
     for (int i = 0; i < 16; i++) o_acc[db][i] = 0.f;
-  constexpr float kSumCap = 65536.f;
+  // Largest sub-tile sum (16 weights of one row) the fast path accepts: 2^80.  The weights, their
+  // bf16 roundings and the fp32 accumulators all carry an 8-bit exponent, so precision does not
+  // depend on the magnitude; the cap only has to keep sums over a whole K/V chunk (up to 2^20 keys,
+  // |v| up to 2^7) below 2^127.  A score must therefore exceed the reference by 55 (in natural
+  // units) before the reference is moved: on all but pathological inputs that happens once, at
+  // the row's first keys.
+  constexpr float kSumCap = 0x1p80f;
   float m_ref = -INFINITY;  // exponent reference of this query, in raw (unscaled) score units
   float mc = 0.f;           // m_ref * c2 (0 while m_ref is -inf), kept alongside m_ref
   float l_run = 0.f;        // this lane's share of the running sum of exp
@@ -303,7 +309,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   // -inf, the slow path runs after the stream: row maximum, raise the reference, rescale l
   // and the O accumulators (which by then include P_{j-1}, consistently), redo the exponentials.
   // Row sums use the unrounded fp32 P: summing the bf16-rounded weights would cost up to
-  // 2^-9 relative in l, more than the 1e-3 budget of lse for rows that see only a few keys.
+  // 2^-8 relative in l, more than the 1e-3 budget of lse for rows that see only a few keys.
   //
   // The stream is written out in the order it should issue - per MFMA: one operand's LDS
   // reads, the MFMA, and a slice of the softmax whose three dependent stages (fma, exp2,

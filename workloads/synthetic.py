@@ -31,6 +31,7 @@ class AttnConfig:
     causal: bool
     std: float
     seed: int
+    profile: str = "normal"   # "normal": Q, K, V ~ N(0, std^2); "wide": Q and K ~ N(0, (3 std)^2); "ramp": see make_qkv_bits
 
     @property
     def scale(self) -> float:
@@ -67,9 +68,16 @@ CONFIGS = {
     "cfg4_merge": MergeConfig("cfg4_merge", 1, 32, 32768, 128, 8, -5.0, 15.0, 20505),
     # GQA long context, 32 query heads / 8 KV heads, seq 131072 as 16 chunks of 8192: 136 steps
     "cfg5_gqa": AttnConfig("cfg5_gqa", 1, 32, 8, 131072, 128, 16, True, 0.5, 20506),
+    # the block step on score distributions that are not N(0,1)-like: scores with a standard deviation of about 9
+    # (Q and K three times wider), and scores that rise slowly and steadily along the keys (about +41 over the chunk)
+    "cfg2_block_wide": AttnConfig("cfg2_block_wide", 1, 32, 32, 4096, 128, 1, False, 1.0, 20508, "wide"),
+    "cfg2_block_ramp": AttnConfig("cfg2_block_ramp", 1, 32, 32, 4096, 128, 1, False, 1.0, 20509, "ramp"),
     # diffusion-transformer shaped: long non-causal sequence, head dim 64, batch 2, four devices (Sec. 3.3.1)
     "dit_ring": AttnConfig("dit_ring", 2, 24, 24, 16384, 64, 4, False, 1.0, 20507),
 }
+
+
+RAMP_STEP = 0.01   # rise of the scaled score per key in the "ramp" profile
 
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
@@ -105,9 +113,18 @@ def _normal_bits(rng: np.random.Generator, shape, std: float) -> np.ndarray:
 def make_qkv_bits(cfg: AttnConfig):
     """Q [B,Hq,S,D], K and V [B,Hkv,S,D] as bf16 bit patterns, drawn in that order from one stream."""
     rng = np.random.Generator(np.random.PCG64(cfg.seed))
-    q = _normal_bits(rng, (cfg.B, cfg.Hq, cfg.S, cfg.D), cfg.std)
-    k = _normal_bits(rng, (cfg.B, cfg.Hkv, cfg.S, cfg.D), cfg.std)
+    qk_std = cfg.std * (3.0 if cfg.profile == "wide" else 1.0)
+    q = _normal_bits(rng, (cfg.B, cfg.Hq, cfg.S, cfg.D), qk_std)
+    k = _normal_bits(rng, (cfg.B, cfg.Hkv, cfg.S, cfg.D), qk_std)
     v = _normal_bits(rng, (cfg.B, cfg.Hkv, cfg.S, cfg.D), cfg.std)
+    if cfg.profile == "ramp":
+        # component 0 of every query is 1 and of key c is c * RAMP_STEP / scale, so the scaled score of key c
+        # carries a term c * RAMP_STEP on top of the N(0,1)-like rest: a slow, steady rise along the keys
+        q[..., 0] = f32_to_bf16_bits(np.ones(1, dtype=np.float32))[0]
+        ramp = (np.arange(cfg.S, dtype=np.float32) * np.float32(RAMP_STEP / cfg.scale))
+        k[..., 0] = f32_to_bf16_bits(ramp)[None, None, :]
+    elif cfg.profile not in ("normal", "wide"):
+        raise ValueError(f"unknown profile {cfg.profile!r}")
     return q, k, v
 
 
