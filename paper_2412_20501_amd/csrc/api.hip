@@ -353,9 +353,13 @@ tr_status tr_block_attn_merge(const tr_tensor* q, const tr_tensor* k, const tr_t
   return attn_common(q, k, v, mask_kind == TR_MASK_CAUSAL_DIAG, 0, scale, out_acc, lse_acc, hip_stream, true);
 }
 
-tr_status tr_merge(const tr_tensor* out_acc, const tr_tensor* lse_acc, const tr_tensor* block_out, const tr_tensor* block_lse,
-                   void* hip_stream) {
-  g_err[0] = 0;
+}  // extern "C"
+
+namespace {
+// acc_streams: the caller knows that the accumulator view is part of a larger tensor that is swept
+// once between two Updates of this view (a ring replay over many Query chunks)
+tr_status merge_common(const tr_tensor* out_acc, const tr_tensor* lse_acc, const tr_tensor* block_out, const tr_tensor* block_lse,
+                       void* hip_stream, bool acc_streams) {
   tr_status st;
   if ((st = check_tensor("out_acc", out_acc, false, true, 16)) != TR_OK) return st;
   if ((st = check_tensor("lse_acc", lse_acc, false, true, 4)) != TR_OK) return st;
@@ -387,10 +391,20 @@ tr_status tr_merge(const tr_tensor* out_acc, const tr_tensor* lse_acc, const tr_
     return t->stride_s == t->D && t->stride_h == t->S * t->D && t->stride_b == t->H * t->S * t->D;
   };
   p.contiguous = dense(out_acc) && dense(block_out) && dense(lse_acc) && dense(block_lse);
+  p.stream_acc = acc_streams ? 1 : 0;
   if (p.B == 0 || p.H == 0 || p.S == 0 || p.D == 0) return TR_OK;
   const hipError_t e = tr::launch_merge(p, block_out->dtype == TR_BF16, (hipStream_t)hip_stream);
   if (e != hipSuccess) return fail(TR_ERR_HIP, "merge launch failed: %s", hipGetErrorString(e));
   return TR_OK;
+}
+}  // namespace
+
+extern "C" {
+
+tr_status tr_merge(const tr_tensor* out_acc, const tr_tensor* lse_acc, const tr_tensor* block_out, const tr_tensor* block_lse,
+                   void* hip_stream) {
+  g_err[0] = 0;
+  return merge_common(out_acc, lse_acc, block_out, block_lse, hip_stream, false);
 }
 
 tr_status tr_merge_n(const tr_tensor* out, const tr_tensor* lse, const tr_tensor* const* block_outs,
@@ -519,6 +533,9 @@ tr_status ring_attn_impl(const tr_tensor* q, const tr_tensor* k, const tr_tensor
     build_schedule(TR_SCHED_TOKENRING, n_chunks, 1, causal != 0, steps);
     return run_steps_fused(q, k, v, out, lse, n_chunks, causal != 0, scale, steps, hip_stream);
   }
+  // between two Updates of one Query chunk every other chunk's accumulator is touched: if all of them
+  // together exceed the memory-side cache, none survives there and the Update streams past the caches
+  const bool out_sweeps = (int64_t)q->B * q->H * q->S * q->D * 4 > ((int64_t)128 << 20);
   for (int i = 0; i < n_chunks; i++) {
     for (int j = 0; j < n_chunks; j++) {
       const int c = ((j - i) % n_chunks + n_chunks) % n_chunks;
@@ -533,7 +550,7 @@ tr_status ring_attn_impl(const tr_tensor* q, const tr_tensor* k, const tr_tensor
       } else {
         st = attn_common(&qc, &kj, &vj, diag, 0, scale, &ws_out, &ws_lse, hip_stream);
         if (st != TR_OK) return st;
-        st = tr_merge(&oc, &lc, &ws_out, &ws_lse, hip_stream);
+        st = merge_common(&oc, &lc, &ws_out, &ws_lse, hip_stream, out_sweeps);
         if (st != TR_OK) return st;
       }
     }

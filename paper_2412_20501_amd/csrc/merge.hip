@@ -15,14 +15,24 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kMergeThreads = 256;
+constexpr int kMergeThreads = 512;
+
+// Accumulators beyond this size cannot stay in the chip's 256 MiB memory-side cache between two
+// Updates, so they are read and written past the caches (non-temporal): measured on the 512 MiB
+// merge-only workload, 5.8 -> 6.5 TB/s.  A smaller accumulator that is updated again soon (one
+// device's Out between two iterations of Algorithm 1) is served from that cache and keeps the
+// ordinary policy, which is the faster one there.
+constexpr int64_t kStreamAccBytes = (int64_t)128 << 20;
 
 // One row is always handled inside a single wavefront: `tpr` (a power of two <= 64) threads
-// share a row and stride over its columns.  Every thread of the row reads the old lse before
-// thread 0 of the row overwrites it, which program order within one wave guarantees.
-// Neighbouring thread groups take neighbouring rows, so a wave touches one contiguous span of
-// each stream.  (Giving a group several rows, near or far apart, measured slower.)
-template <bool BLK_BF16>
+// share a row; a thread takes the 16-byte column chunks t and t + tpr (then t + 2 tpr, ... for
+// long rows), both loads of a pair issued before the first store, so the lse arithmetic of a
+// row (two exponentials and a logarithm per thread) is spread over 32 bytes of every stream.
+// Every thread of the row reads the old lse before thread 0 of the row overwrites it, which
+// program order within one wave guarantees.  Neighbouring thread groups take neighbouring
+// rows, so a wave touches one contiguous span of each stream.  (Giving a group several rows,
+// near or far apart, measured slower; so did one or four chunks per thread.)
+template <bool BLK_BF16, bool STREAM_ACC>
 __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const MergeParams p, int64_t n_rows, int tpr_log2) {
   const int64_t gtid = (int64_t)blockIdx.x * kMergeThreads + threadIdx.x;
   const int64_t row = gtid >> tpr_log2;
@@ -43,17 +53,30 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const MergeParams 
   }
   const UpdatePlan plan = plan_update(p.acc_lse[al], p.blk_lse[bl]);
 
-  for (int col = t * 4; col < p.D; col += tpr * 4) {
-    const f32x4 x = *reinterpret_cast<const f32x4*>(p.acc_out + ao + col);
-    f32x4 y;
+  auto load_acc = [&](int col) __attribute__((always_inline)) -> f32x4 {
+    const f32x4* src = reinterpret_cast<const f32x4*>(p.acc_out + ao + col);
+    return STREAM_ACC ? __builtin_nontemporal_load(src) : *src;
+  };
+  auto load_blk = [&](int col) __attribute__((always_inline)) -> f32x4 {
     if (BLK_BF16) {
       const bf16x4 yb = __builtin_nontemporal_load(reinterpret_cast<const bf16x4*>(reinterpret_cast<const __bf16*>(p.blk_out) + bo + col));
-#pragma unroll
-      for (int i = 0; i < 4; i++) y[i] = (float)yb[i];
-    } else {
-      y = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(p.blk_out) + bo + col));
+      return f32x4{(float)yb[0], (float)yb[1], (float)yb[2], (float)yb[3]};
     }
-    *reinterpret_cast<f32x4*>(p.acc_out + ao + col) = apply_update(plan, x, y);
+    return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(p.blk_out) + bo + col));
+  };
+  auto store_acc = [&](int col, f32x4 val) __attribute__((always_inline)) {
+    f32x4* dst = reinterpret_cast<f32x4*>(p.acc_out + ao + col);
+    if (STREAM_ACC) __builtin_nontemporal_store(val, dst);
+    else *dst = val;
+  };
+  for (int col = t * 4; col < p.D; col += tpr * 8) {
+    const int col2 = col + tpr * 4;
+    const bool two = col2 < p.D;
+    const f32x4 x0 = load_acc(col), y0 = load_blk(col);
+    f32x4 x1 = x0, y1 = y0;
+    if (two) { x1 = load_acc(col2); y1 = load_blk(col2); }
+    store_acc(col, apply_update(plan, x0, y0));
+    if (two) store_acc(col2, apply_update(plan, x1, y1));
   }
   if (t == 0) p.acc_lse[al] = plan.new_lse;
 }
@@ -172,13 +195,19 @@ hipError_t launch_merge_n(const MergeNParams& p, bool blk_bf16, hipStream_t stre
 hipError_t launch_merge(const MergeParams& p, bool blk_bf16, hipStream_t stream) {
   const int64_t n_rows = (int64_t)p.B * p.H * p.S;
   if (n_rows == 0 || p.D == 0) return hipSuccess;
+  // threads per row: half the row's 16-byte chunks (two chunks per thread), a power of two, at most a wave
   int tpr_log2 = 0;
-  while ((1 << tpr_log2) < p.D / 4 && tpr_log2 < 6) tpr_log2++;
+  while ((1 << tpr_log2) < p.D / 8 && tpr_log2 < 6) tpr_log2++;
   const int64_t n_threads = n_rows << tpr_log2;
   const int64_t nblocks = (n_threads + kMergeThreads - 1) / kMergeThreads;
   dim3 grid((unsigned)nblocks), block(kMergeThreads);
-  if (blk_bf16) return launch_kernel(merge_kernel<true>, grid, block, 0, stream, p, n_rows, tpr_log2);
-  return launch_kernel(merge_kernel<false>, grid, block, 0, stream, p, n_rows, tpr_log2);
+  const bool stream_acc = p.stream_acc || n_rows * p.D * 4 > kStreamAccBytes;
+  if (blk_bf16) {
+    if (stream_acc) return launch_kernel(merge_kernel<true, true>, grid, block, 0, stream, p, n_rows, tpr_log2);
+    return launch_kernel(merge_kernel<true, false>, grid, block, 0, stream, p, n_rows, tpr_log2);
+  }
+  if (stream_acc) return launch_kernel(merge_kernel<false, true>, grid, block, 0, stream, p, n_rows, tpr_log2);
+  return launch_kernel(merge_kernel<false, false>, grid, block, 0, stream, p, n_rows, tpr_log2);
 }
 
 }  // namespace tr

@@ -52,6 +52,7 @@ struct MergeParams {
   int64_t bl_sb, bl_sh, bl_ss;
   int B, H, S, D;
   int contiguous;  // 1: all four tensors are dense [B*H*S, D] / [B*H*S]
+  int stream_acc;  // 1: the caller knows the accumulator is not touched again soon (access past the caches)
 };
 
 // Arguments of the n-ary merge kernel: up to kMergeNMax partial results with common strides.
