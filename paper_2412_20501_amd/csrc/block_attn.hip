@@ -578,7 +578,8 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   constexpr int CPRF = D / 4;                 // 16-byte chunks per fp32 row = lanes per row when reading back
   constexpr int RPI_OUT = 64 / CPRF;          // rows one wave-wide access covers
   char* const my = lds + wave * (32 * ROWB);
-  float* const my_lse = reinterpret_cast<float*>(lds + kWaves * 32 * ROWB) + wave * 32;
+  float* const my_w = reinterpret_cast<float*>(lds + kWaves * 32 * ROWB) + wave * 32;   // Update weight of each of the wave's rows
+  int* const my_mode = reinterpret_cast<int*>(lds + kWaves * 32 * ROWB) + (kWaves + wave) * 32;   // and its case
   const float l_tot = half_swap_sum(l_run);
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   const float lse_blk = l_tot > 0.f ? m_ref * p.scale + logf(l_tot) : -INFINITY;
@@ -592,8 +593,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
       for (int r = 0; r < 4; r++) o[r] = o_acc[db][4 * g + r] * inv;
       *reinterpret_cast<f32x4*>(my + ql * ROWB + ((c ^ (ql & 15)) << 4)) = o;
     }
-  if (hf == 0) my_lse[ql] = lse_blk;
-  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the wave's own LDS writes are visible to all its lanes
+  if (EPI != kEpiMerge) __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the wave's own LDS writes are visible to all its lanes
   if (EPI != kEpiMerge && hf == 0 && qrow < p.Sq)
     p.lse[qseg * p.l_seg_elems + (int64_t)b * p.l_sb + (int64_t)hq * p.l_sh + (int64_t)qrow * p.l_ss] = lse_blk;
   const int rr = lane / CPRF, cc = lane % CPRF;
@@ -608,24 +608,36 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     // per launch, so it is read and written past the caches (non-temporal).
     float* const acc_out = reinterpret_cast<float*>(p.out);
     f32x4 x[NIT];
-    float la[NIT];
 #pragma unroll
     for (int it = 0; it < NIT; it++) {
       const int grow = min(qw0 + it * RPI_OUT + rr, p.Sq - 1);
       x[it] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(acc_out + o_bh + (int64_t)grow * p.o_ss));
-      la[it] = p.lse[l_bh + (int64_t)grow * p.l_ss];
     }
+    // The Update of a row is planned once, by the lanes that own the row in the accumulator layout
+    // (its two exponentials and its logarithm would otherwise be evaluated in every lane that
+    // blends a chunk of the row, 16 times per wave at D = 128), while the accumulator pieces are
+    // on their way.  The same lane reads the row's old lse and writes the new one.
+    {
+      const int64_t l_at = l_bh + (int64_t)min(qrow, p.Sq - 1) * p.l_ss;
+      const UpdatePlan plq = plan_update(p.lse[l_at], lse_blk);
+      if (hf == 0) {
+        my_w[ql] = plq.w;
+        my_mode[ql] = plq.mode;
+        if (qrow < p.Sq) p.lse[l_at] = plq.new_lse;
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the wave's own LDS writes are visible to all its lanes
 #pragma unroll
     for (int it = 0; it < NIT; it++) {
       const int r = it * RPI_OUT + rr;
       const int grow = qw0 + r;
       const f32x4 o = *reinterpret_cast<const f32x4*>(my + r * ROWB + ((cc ^ (r & 15)) << 4));
-      const UpdatePlan pl = plan_update(la[it], my_lse[r]);
-      if (grow < p.Sq) {
+      UpdatePlan pl;
+      pl.w = my_w[r];
+      pl.mode = my_mode[r];
+      pl.new_lse = 0.f;
+      if (grow < p.Sq)
         __builtin_nontemporal_store(apply_update(pl, x[it], o), reinterpret_cast<f32x4*>(acc_out + o_bh + (int64_t)grow * p.o_ss));
-        // every lane of the row took the old lse in the first loop, so the single write is safe
-        if (cc == 0) p.lse[l_bh + (int64_t)grow * p.l_ss] = pl.new_lse;
-      }
     }
   } else if (EPI == kEpiF32) {
 #pragma unroll
@@ -662,7 +674,7 @@ template <int D, int EPI>
 hipError_t launch_one(const AttnParams& p, dim3 grid, hipStream_t stream) {
   // K/V rings; the epilogue reuses them for kWaves private 32 x D fp32 tiles plus 32 lse each
   constexpr int ring_bytes = 2 * kRing * tile_keys<D>() * 2 * D;
-  constexpr int epi_bytes = kWaves * 32 * 4 * D + kWaves * 32 * 4;
+  constexpr int epi_bytes = kWaves * 32 * 4 * D + 2 * kWaves * 32 * 4;
   constexpr int lds_bytes = ring_bytes > epi_bytes ? ring_bytes : epi_bytes;
   static_assert(lds_bytes <= 160 * 1024, "LDS budget of one CU exceeded");
   // Raising the dynamic-LDS limit is a per-function, per-device setting: done once for each
