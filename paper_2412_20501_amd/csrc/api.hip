@@ -142,6 +142,11 @@ tr_status attn_common(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v
   const int bm = tr::attn_rows_per_block();
   p.n_qtiles = (p.Sq + bm - 1) / bm;
   p.xcd_map = (p.B * p.Hkv) % 8 == 0 && (int64_t)p.n_qtiles * p.B * p.Hq >= 8;
+  p.gq = p.Hkv > 0 ? p.Hq / p.Hkv : 1;
+  p.gq_log2 = -1;
+  for (int sh = 0; sh < 31; sh++)
+    if (p.gq == (1 << sh)) p.gq_log2 = sh;
+  if (p.n_qtiles > 65535) return fail(TR_ERR_SHAPE, "Sq too long for one launch (at most 65535 query tiles of %d rows)", bm);
   p.n_prob = 1;
   p.blocks_per_prob = p.n_qtiles * p.B * p.Hq;
   p.causal_bits = p.causal ? 1u : 0u;

@@ -93,24 +93,27 @@ __device__ __forceinline__ int v_lds_off(int row, int c) {
   return row * RB + ((slot ^ swz) << 5) + ((c & 1) << 4);
 }
 
-__device__ __forceinline__ void decode_block(const AttnParams& p, int bid, int& qt, int& bh) {
-  const int nbh = p.B * p.Hq;
-  int qt_rank;
+// Which (batch*head, query tile, block step) a workgroup computes.  The grid is three-dimensional
+// - x: batch*head, y: query tile, z: block step of the launch - so the indices come from the
+// hardware instead of integer divisions (a division costs ~40 dependent instructions and the
+// decoding sits in front of every workgroup's first load).  Workgroups are dealt round-robin to
+// the 8 XCDs in the order of their linear id, which is x-fastest, and the x extent is a multiple
+// of 8 whenever xcd_map is set: XCD = blockIdx.x mod 8.  XCD x gets the K/V heads x, x+8, ... and
+// all query heads and query tiles that read them, so a head's K/V stays in one L2.
+__device__ __forceinline__ void decode_block(const AttnParams& p, int& qt, int& b, int& hq, int& hk, int& prob) {
+  const int gq = p.gq, sh = p.gq_log2;   // query heads per K/V head; its log2, or -1 if not a power of two
+  int bh = (int)blockIdx.x;
   if (p.xcd_map) {
-    // Workgroups are dealt round-robin to the 8 XCDs; give XCD x the K/V heads x, x+8, ...
-    // and all query heads / query tiles that read them, so a head's K/V stays in one L2.
-    const int G = p.Hq / p.Hkv;
-    const int x = bid & 7, slot = bid >> 3;
-    const int per_xcd = nbh >> 3;
-    qt_rank = slot / per_xcd;
-    const int hi = slot % per_xcd;
-    const int kv = (hi / G) * 8 + x;
-    bh = kv * G + hi % G;
-  } else {
-    qt_rank = bid / nbh;
-    bh = bid % nbh;
+    const int x = bh & 7, hi = bh >> 3;
+    const int kvi = sh >= 0 ? hi >> sh : hi / gq;
+    const int mem = sh >= 0 ? hi & (gq - 1) : hi % gq;
+    bh = (kvi * 8 + x) * gq + mem;
   }
-  qt = p.n_qtiles - 1 - qt_rank;  // late query tiles (most keys under a causal mask) first
+  b = p.B == 1 ? 0 : bh / p.Hq;
+  hq = bh - b * p.Hq;
+  hk = sh >= 0 ? hq >> sh : hq / gq;
+  qt = p.n_qtiles - 1 - (int)blockIdx.y;  // late query tiles (most keys under a causal mask) first
+  prob = (int)blockIdx.z;
 }
 
 typedef __attribute__((address_space(1))) const void* gptr_t;
@@ -155,15 +158,11 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in an SGPR
   const int ql = lane & 31, hf = lane >> 5;
 
-  // which of the launch's block steps this workgroup belongs to (wave-uniform)
-  const int prob = p.n_prob > 1 ? (int)(blockIdx.x / (unsigned)p.blocks_per_prob) : 0;
-  const int bid = p.n_prob > 1 ? (int)(blockIdx.x - (unsigned)prob * (unsigned)p.blocks_per_prob) : (int)blockIdx.x;
+  // which block step of the launch, batch, head and query tile this workgroup computes (wave-uniform)
+  int qt, b, hq, hk, prob;
+  decode_block(p, qt, b, hq, hk, prob);
   const int64_t qseg = p.q_seg[prob], kseg = p.k_seg[prob];
   const bool causal = (p.causal_bits >> prob) & 1u;
-
-  int qt, bh;
-  decode_block(p, bid, qt, bh);
-  const int b = bh / p.Hq, hq = bh % p.Hq, hk = hq / (p.Hq / p.Hkv);
   const int q0 = qt * kBM, qw0 = q0 + wave * 32;
   const int qrow = qw0 + ql;
   const int qrow_ld = min(qrow, p.Sq - 1);
@@ -696,9 +695,10 @@ hipError_t launch_one(const AttnParams& p, dim3 grid, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_block_attn(const AttnParams& p, int D, int epilogue, hipStream_t stream) {
-  const int64_t nblocks = (int64_t)p.n_qtiles * p.B * p.Hq * p.n_prob;
-  if (nblocks == 0) return hipSuccess;
-  dim3 grid((unsigned)nblocks);
+  const int64_t nbh = (int64_t)p.B * p.Hq;
+  if (nbh * p.n_qtiles * p.n_prob == 0) return hipSuccess;
+  if (p.n_qtiles > 65535 || p.n_prob > 65535) return hipErrorInvalidValue;   // grid y / z limits
+  dim3 grid((unsigned)nbh, (unsigned)p.n_qtiles, (unsigned)p.n_prob);
   if (D == 128) {
     if (epilogue == kEpiBf16) return launch_one<128, kEpiBf16>(p, grid, stream);
     if (epilogue == kEpiF32) return launch_one<128, kEpiF32>(p, grid, stream);

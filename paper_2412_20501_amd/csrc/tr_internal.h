@@ -28,8 +28,10 @@ struct AttnParams {
   float scale;    // softmax scale (natural units)
   int n_qtiles;   // ceil(Sq / rows per workgroup)
   int xcd_map;    // 1: place all query tiles of a K/V head on one XCD
+  int gq;         // query heads per K/V head (Hq / Hkv)
+  int gq_log2;    // log2(gq) if gq is a power of two, else -1
   // Several independent block steps of equal shape in one launch (the steps different "devices"
-  // run in the same iteration of a schedule): problem g = blockIdx / blocks_per_prob works on the
+  // run in the same iteration of a schedule): problem g = blockIdx.z works on the
   // Query segment q_seg[g] (q, out, lse advanced by q_seg[g] * *_seg elements) and the K/V
   // segment k_seg[g], with the causal rule iff bit g of causal_bits is set.  n_prob = 1 with
   // q_seg[0] = k_seg[0] = 0 and causal_bits = causal is the plain single step.
