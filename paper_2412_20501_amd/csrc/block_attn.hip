@@ -167,32 +167,11 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   const int qrow = qw0 + ql;
   const int qrow_ld = min(qrow, p.Sq - 1);
 
-  // Q^T fragments: lane (q, hf) holds Q[q][16*ks + 8*hf .. +7] for every k-step.
-  bf16x8 qf[KS];
-  {
-    const __bf16* qp = p.q + qseg * p.q_seg_elems + (int64_t)b * p.q_sb + (int64_t)hq * p.q_sh + (int64_t)qrow_ld * p.q_ss;
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks + 8 * hf);
-  }
-
-  // Key range of this workgroup (in 64-key tiles) and of this wave (in 32-key sub-tiles).
+  // Key range of this workgroup in tiles (needed to start the loads; the wave's own range follows below)
   const int q_last_wg = min(q0 + kBM, p.Sq) - 1;
   int kv_end = p.Sk;
   if (causal) kv_end = max(0, min(p.Sk, q_last_wg + p.causal_off + 1));
   const int n_tiles = (kv_end + BN - 1) / BN;
-  int wave_kv_end = 0;
-  if (qw0 < p.Sq) {
-    wave_kv_end = p.Sk;
-    if (causal) wave_kv_end = max(0, min(p.Sk, min(qw0 + 31, p.Sq - 1) + p.causal_off + 1));
-  }
-  const int jw = (wave_kv_end + SUB - 1) / SUB;  // sub-tiles this wave has visible keys in
-  // wave-uniform loop bounds, forced into scalar registers so that every per-step test is one compare
-  const int jw_first = __builtin_amdgcn_readfirstlane(jw);                            // last allowed step that opens a tile
-  const int jw_in = __builtin_amdgcn_readfirstlane(min(jw, NSUB * n_tiles - 1));      // last allowed step inside a tile
-  // a sub-tile starting at kstart needs masking iff kstart > kmask_from
-  int kmask_from_v = p.Sk - SUB;
-  if (causal) kmask_from_v = min(kmask_from_v, qw0 + p.causal_off - SUB + 1);
-  const int kmask_from = __builtin_amdgcn_readfirstlane(kmask_from_v);
 
   const __bf16* kg = p.k + kseg * p.k_seg_elems + (int64_t)b * p.k_sb + (int64_t)hk * p.k_sh;
   const __bf16* vg = p.v + kseg * p.v_seg_elems + (int64_t)b * p.v_sb + (int64_t)hk * p.v_sh;
@@ -253,6 +232,40 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     v_next = uniform_ptr(v_next + (last ? 0 : v_tile_stride));
     v_left--;
   };
+
+  // ---- prologue: K_0..K_2, V_0, V_1 into the rings, then the Query fragments.  The loads go out
+  // before the rest of the set-up (this wave's key range, LDS read addresses, cleared accumulators)
+  // so that their latency, the longest wait of a workgroup's life, runs under that arithmetic.
+  if (n_tiles > 0) {
+    issue_k(0);
+    issue_v(0);
+    issue_k(1);
+    issue_v(1);
+    issue_k(2);
+  }
+  // Q^T fragments: lane (q, hf) holds Q[q][16*ks + 8*hf .. +7] for every k-step.
+  bf16x8 qf[KS];
+  {
+    const __bf16* qp = p.q + qseg * p.q_seg_elems + (int64_t)b * p.q_sb + (int64_t)hq * p.q_sh + (int64_t)qrow_ld * p.q_ss;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks + 8 * hf);
+  }
+
+
+  // Key range of this wave (in 32-key sub-tiles).
+  int wave_kv_end = 0;
+  if (qw0 < p.Sq) {
+    wave_kv_end = p.Sk;
+    if (causal) wave_kv_end = max(0, min(p.Sk, min(qw0 + 31, p.Sq - 1) + p.causal_off + 1));
+  }
+  const int jw = (wave_kv_end + SUB - 1) / SUB;  // sub-tiles this wave has visible keys in
+  // wave-uniform loop bounds, forced into scalar registers so that every per-step test is one compare
+  const int jw_first = __builtin_amdgcn_readfirstlane(jw);                            // last allowed step that opens a tile
+  const int jw_in = __builtin_amdgcn_readfirstlane(min(jw, NSUB * n_tiles - 1));      // last allowed step inside a tile
+  // a sub-tile starting at kstart needs masking iff kstart > kmask_from
+  int kmask_from_v = p.Sk - SUB;
+  if (causal) kmask_from_v = min(kmask_from_v, qw0 + p.causal_off - SUB + 1);
+  const int kmask_from = __builtin_amdgcn_readfirstlane(kmask_from_v);
 
   // Per-lane LDS read offsets.
   // K operand: lane (key = ql, hf) reads chunk 2*ks + hf of row 32*kt + ql.
@@ -457,14 +470,6 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     v_left--;
   };
 
-  // ---- prologue: K_0..K_2, V_0, V_1 into the rings
-  if (n_tiles > 0) {
-    issue_k(0);
-    issue_v(0);
-    issue_k(1);
-    issue_v(1);
-    issue_k(2);
-  }
 #pragma unroll
   for (int ks = 0; ks < KS; ks++) asm volatile("" ::"v"(qf[ks]));  // Q is in registers before the loop
   __builtin_amdgcn_s_waitcnt(0);
