@@ -212,8 +212,12 @@ typedef enum {
  *   TR_SCHED_RING_ATTENTION for i, for j: Q chunk j  x  K/V chunk (j-i) mod n
  *   TR_SCHED_ZIGZAG         for i, for j: the Query pair {c, 2n-1-c}, c = (j-i) mod n, against the K/V pair
  *                           {j, 2n-1-j}; of the four segment pairs the causal rule keeps two full ones
- *                           (three on i == 0, two of them diagonal), so every (i, j) carries the same work; within
- *                           an iteration the devices' pairs are issued slot by slot (all first pairs, then all second, ...)
+ *                           (three on i == 0, two of them diagonal), so every (i, j) carries the same work.  When the
+ *                           later Query segment meets both K/V segments of the device and the segment length is a
+ *                           multiple of 128, the two are attended in ONE block step over the device's whole K/V (one
+ *                           softmax over both, one Update), which Eq. (1)-(3) leave unchanged; an iteration is then
+ *                           a single launch of at most two steps per device.  Otherwise the devices' pairs are issued
+ *                           slot by slot (all first pairs, then all second, ...)
  *   TR_SCHED_HYBRID         n_devices = nodes x n_inner; for t < nodes, for i < n_inner, for node, for p:
  *                           Q chunk node*n_inner + (p-i) mod n_inner  x  K/V chunk ((node-t) mod nodes)*n_inner + p
  *                           (n_inner is ignored by the other schedules)
@@ -234,7 +238,10 @@ tr_status tr_ring_attn_sched(const tr_tensor* q, const tr_tensor* k, const tr_te
  *   the attention launch that carries the step
  * (steps of one launch touch distinct Query segments and run concurrently; launches run in
  * order).  Segments are n_devices equal chunks of S, 2 * n_devices for TR_SCHED_ZIGZAG; with
- * causal != 0 a step with equal segments is the diagonal-masked one.  Touches no device.
+ * causal != 0 a step with equal segments is the diagonal-masked one.  For TR_SCHED_ZIGZAG the
+ * list is the one for segment lengths that are multiples of 128: a block step over a pair of
+ * K/V segments appears as its two (Query segment, K/V segment) entries, adjacent and in the
+ * same launch, the only case of a Query segment occurring twice in a launch.  Touches no device.
  */
 int64_t tr_schedule_steps(int schedule, int n_devices, int n_inner, int causal, int32_t* steps_out, int64_t capacity);
 

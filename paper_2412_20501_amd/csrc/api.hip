@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <atomic>
 #include <vector>
 
@@ -86,12 +87,17 @@ tr_status check_written(const char* name, const tr_tensor* t) {
   return TR_OK;
 }
 
-// One block step of a schedule: Query segment qs attends K/V segment ks (equal segments of S).
-struct RingStep { int qs, ks; };
+// One block step of a schedule: Query segment qs attends K/V segment ks (equal segments of S),
+// or, with ks2 >= 0, the pair of K/V segments ks and ks2 as one key range.
+struct RingStep {
+  int qs, ks;
+  int ks2 = -1;
+};
 
 // Several block steps of one shape for a single launch: the tensors handed to attn_common are
 // the views of segment 0 (length seg_len along S); step i works on Query segment steps[i].qs
-// and K/V segment steps[i].ks, masked diagonally iff `causal` and both are equal.
+// and K/V segment steps[i].ks, masked diagonally iff `causal` and both are equal; a step with a
+// second K/V segment is masked iff that one equals the Query segment (the first lies before it).
 struct StepGroup {
   const RingStep* steps;
   int n;
@@ -148,6 +154,7 @@ tr_status attn_common(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v
     if (p.gq == (1 << sh)) p.gq_log2 = sh;
   if (p.n_qtiles > 65535) return fail(TR_ERR_SHAPE, "Sq too long for one launch (at most 65535 query tiles of %d rows)", bm);
   p.n_prob = 1;
+  for (int i = 0; i < tr::kAttnGroupMax; i++) p.k_seg2[i] = -1;
   p.blocks_per_prob = p.n_qtiles * p.B * p.Hq;
   p.causal_bits = p.causal ? 1u : 0u;
   if (group) {
@@ -157,10 +164,19 @@ tr_status attn_common(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v
     p.q_seg_elems = group->seg_len * q->stride_s; p.k_seg_elems = group->seg_len * k->stride_s;
     p.v_seg_elems = group->seg_len * v->stride_s; p.o_seg_elems = group->seg_len * out->stride_s;
     p.l_seg_elems = group->seg_len * lse->stride_s;
+    // Workgroups are dispatched step by step, so the steps go in longest first: a launch then ends
+    // on its short steps and the tail in which some compute units are idle is as short as possible.
+    const RingStep* order[tr::kAttnGroupMax];
+    auto cost = [&](const RingStep& s) { return (s.ks2 >= 0 ? 4 : 2) - ((group->causal && (s.ks2 >= 0 ? s.ks2 : s.ks) == s.qs) ? 1 : 0); };
+    for (int i = 0; i < group->n; i++) order[i] = group->steps + i;
+    std::stable_sort(order, order + group->n, [&](const RingStep* a, const RingStep* b) { return cost(*a) > cost(*b); });
     for (int i = 0; i < group->n; i++) {
-      p.q_seg[i] = (short)group->steps[i].qs;
-      p.k_seg[i] = (short)group->steps[i].ks;
-      if (group->causal && group->steps[i].qs == group->steps[i].ks) p.causal_bits |= 1u << i;
+      const RingStep& s = *order[i];
+      if (s.ks2 >= 0 && (group->seg_len % 128 || s.ks2 <= s.ks)) return fail(TR_ERR_SHAPE, "internal: segment pair on segments of %lld keys", (long long)group->seg_len);
+      p.q_seg[i] = (short)s.qs;
+      p.k_seg[i] = (short)s.ks;
+      p.k_seg2[i] = (short)s.ks2;
+      if (group->causal && (s.ks2 >= 0 ? s.ks2 : s.ks) == s.qs) p.causal_bits |= 1u << i;
     }
   }
   if ((int64_t)p.blocks_per_prob * p.n_prob >= ((int64_t)1 << 31)) return fail(TR_ERR_SHAPE, "too many workgroups for one launch");
@@ -190,7 +206,7 @@ inline int pmod(int a, int n) { return ((a % n) + n) % n; }
 //     Query pair circulates as in Algorithm 1.
 //   Hybrid (Sec. 3.3.3): n = nodes * n_inner devices; K/V travel between nodes as in Ring
 //     Attention (outer step t), Algorithm 1 runs among the n_inner devices of each node.
-int build_schedule(int schedule, int n, int n_inner, bool causal, std::vector<RingStep>& steps) {
+int build_schedule(int schedule, int n, int n_inner, bool causal, std::vector<RingStep>& steps, bool pair_kv = false) {
   steps.clear();
   auto add = [&](int qs, int ks) {
     if (!causal || ks <= qs) steps.push_back({qs, ks});
@@ -209,15 +225,23 @@ int build_schedule(int schedule, int n, int n_inner, bool causal, std::vector<Ri
       // its own Query pair; they are emitted slot by slot (every device's first pair, then every
       // device's second, ...) so that pairs on distinct Query segments are adjacent and can share
       // a launch.  The order of the blocks each Query segment receives is unaffected.
+      // pair_kv: when a Query segment meets both K/V segments of the device (always its later
+      // segment), the two become one block step over the device's whole K/V; a device then has at
+      // most two steps per iteration, on its two Query segments.
       for (int i = 0; i < n; i++) {
         for (int slot = 0; slot < 4; slot++) {
           for (int j = 0; j < n; j++) {
             const int c = pmod(j - i, n);
             const int qseg[2] = {c, 2 * n - 1 - c}, kseg[2] = {j, 2 * n - 1 - j};
+            RingStep dev[4];
             int kept = 0;
             for (int a = 0; a < 2; a++)
-              for (int b = 0; b < 2; b++)
-                if (kseg[b] <= qseg[a] && kept++ == slot) steps.push_back({qseg[a], kseg[b]});
+              for (int b = 0; b < 2; b++) {
+                if (kseg[b] > qseg[a]) continue;
+                if (pair_kv && b == 1 && kept > 0 && dev[kept - 1].qs == qseg[a] && dev[kept - 1].ks2 < 0) dev[kept - 1].ks2 = kseg[b];
+                else dev[kept++] = {qseg[a], kseg[b]};
+              }
+            if (slot < kept) steps.push_back(dev[slot]);
           }
         }
       }
@@ -609,17 +633,18 @@ int64_t tr_schedule_steps(int schedule, int n_devices, int n_inner, int causal, 
     return -1;
   }
   std::vector<RingStep> steps;
-  const int n_seg = build_schedule(schedule, n_devices, n_inner, causal != 0, steps);
-  if (steps_out && capacity > 0) {
-    const std::vector<LaunchGroup> groups = group_steps(steps, n_seg);
-    for (size_t g = 0; g < groups.size(); g++)
-      for (size_t i = groups[g].begin; i < groups[g].end && (int64_t)i < capacity; i++) {
-        steps_out[3 * i] = steps[i].qs;
-        steps_out[3 * i + 1] = steps[i].ks;
-        steps_out[3 * i + 2] = (int32_t)g;
-      }
-  }
-  return (int64_t)steps.size();
+  const int n_seg = build_schedule(schedule, n_devices, n_inner, causal != 0, steps, true);
+  const std::vector<LaunchGroup> groups = group_steps(steps, n_seg);
+  int64_t n_out = 0;   // a step on a pair of K/V segments is reported as its two segment pairs
+  for (size_t g = 0; g < groups.size(); g++)
+    for (size_t i = groups[g].begin; i < groups[g].end; i++)
+      for (int half = 0; half < (steps[i].ks2 >= 0 ? 2 : 1); half++, n_out++)
+        if (steps_out && n_out < capacity) {
+          steps_out[3 * n_out] = steps[i].qs;
+          steps_out[3 * n_out + 1] = half ? steps[i].ks2 : steps[i].ks;
+          steps_out[3 * n_out + 2] = (int32_t)g;
+        }
+  return n_out;
 }
 
 tr_status tr_ring_attn_sched(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v, int n_devices, int causal,
@@ -651,7 +676,8 @@ tr_status tr_ring_attn_sched(const tr_tensor* q, const tr_tensor* k, const tr_te
   if (overlaps(out, q) || overlaps(out, k) || overlaps(out, v) || overlaps(lse, q) || overlaps(lse, k) || overlaps(lse, v) || overlaps(out, lse))
     return fail(TR_ERR_ALIAS, "outputs overlap inputs or each other");
   std::vector<RingStep> steps;
-  build_schedule(schedule, n_devices, n_inner, causal != 0, steps);
+  // segments that are whole K/V tiles of either head dim can be attended in pairs
+  build_schedule(schedule, n_devices, n_inner, causal != 0, steps, (q->S / n_seg) % 128 == 0);
   return run_steps_fused(q, k, v, out, lse, n_seg, causal != 0, scale, steps, hip_stream);
 }
 

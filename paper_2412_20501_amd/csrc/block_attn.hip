@@ -163,14 +163,21 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   decode_block(p, qt, b, hq, hk, prob);
   const int64_t qseg = p.q_seg[prob], kseg = p.k_seg[prob];
   const bool causal = (p.causal_bits >> prob) & 1u;
+  // A block step may attend a pair of K/V segments as one key range (the two segments a device of
+  // the zigzag partition holds): keys 0 .. p.Sk-1 are segment kseg, keys p.Sk .. 2 p.Sk-1 segment
+  // kseg2, which lies p.Sk positions later in the causal rule.  p.Sk is then a multiple of the
+  // tile, so the tile stream changes segment between two tiles.
+  const int kseg2 = p.k_seg2[prob];
+  const int Sk = kseg2 >= 0 ? 2 * p.Sk : p.Sk;
+  const int causal_off = kseg2 >= 0 ? p.Sk : p.causal_off;
   const int q0 = qt * kBM, qw0 = q0 + wave * 32;
   const int qrow = qw0 + ql;
   const int qrow_ld = min(qrow, p.Sq - 1);
 
   // Key range of this workgroup in tiles (needed to start the loads; the wave's own range follows below)
   const int q_last_wg = min(q0 + kBM, p.Sq) - 1;
-  int kv_end = p.Sk;
-  if (causal) kv_end = max(0, min(p.Sk, q_last_wg + p.causal_off + 1));
+  int kv_end = Sk;
+  if (causal) kv_end = max(0, min(Sk, q_last_wg + causal_off + 1));
   const int n_tiles = (kv_end + BN - 1) / BN;
 
   const __bf16* kg = p.k + kseg * p.k_seg_elems + (int64_t)b * p.k_sb + (int64_t)hk * p.k_sh;
@@ -184,7 +191,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   // arithmetic.  Rows past the end of the keys re-read the last key (they are masked later):
   // the last, possibly partial, tile has its own clamped offsets, and tiles beyond it (the
   // ring runs ahead of the loop) re-read the last tile.
-  const int last_tile = (p.Sk - 1) / BN;
+  const int last_tile = (Sk - 1) / BN;
   unsigned k_off[IPW], v_off[IPW], k_off_last[IPW], v_off_last[IPW];
 #pragma unroll
   for (int i = 0; i < IPW; i++) {
@@ -192,7 +199,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     const int kc = (pc ^ ((row / (256 / RB)) % CPR)) * 8;
     const int vswz = (D == 128) ? ((row & 3) << 1) : (row & 2);
     const int vc = ((((pc >> 1) ^ vswz) << 1) | (pc & 1)) * 8;
-    const int row_last = max(0, min(row, p.Sk - 1 - last_tile * BN));
+    const int row_last = max(0, min(row, Sk - 1 - last_tile * BN));
     k_off[i] = (unsigned)(((int64_t)row * p.k_ss + kc) * 2);
     v_off[i] = (unsigned)(((int64_t)row * p.v_ss + vc) * 2);
     k_off_last[i] = (unsigned)(((int64_t)row_last * p.k_ss + kc) * 2);
@@ -216,12 +223,16 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   const __bf16* v_next = uniform_ptr(vg);
   const int64_t k_tile_stride = (int64_t)BN * p.k_ss, v_tile_stride = (int64_t)BN * p.v_ss;
   int k_left = last_tile, v_left = last_tile;  // tiles still ahead of the pointer
+  // with a segment pair: the pointer leaves the first segment when jump_left tiles are still ahead
+  // (the counters run below zero when the ring issues past the last tile, so "never" is a value they cannot take)
+  const int jump_left = kseg2 >= 0 ? last_tile + 1 - p.Sk / BN : 0x7fffffff;
+  const int64_t k_jump = (int64_t)(kseg2 - (int)kseg - 1) * p.k_seg_elems, v_jump = (int64_t)(kseg2 - (int)kseg - 1) * p.v_seg_elems;
   auto issue_k = [&](int slot) __attribute__((always_inline)) {
     const bool last = k_left <= 0;
 #pragma unroll
     for (int i = 0; i < IPW; i++)
       dma16(k_next, last ? k_off_last[i] : k_off[i], slot * TILE_BYTES + (wave * IPW + i) * 1024);
-    k_next = uniform_ptr(k_next + (last ? 0 : k_tile_stride));
+    k_next = uniform_ptr(k_next + (last ? 0 : k_tile_stride) + (k_left == jump_left ? k_jump : 0));
     k_left--;
   };
   auto issue_v = [&](int slot) __attribute__((always_inline)) {
@@ -229,7 +240,7 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
 #pragma unroll
     for (int i = 0; i < IPW; i++)
       dma16(v_next, last ? v_off_last[i] : v_off[i], (NS + slot) * TILE_BYTES + (wave * IPW + i) * 1024);
-    v_next = uniform_ptr(v_next + (last ? 0 : v_tile_stride));
+    v_next = uniform_ptr(v_next + (last ? 0 : v_tile_stride) + (v_left == jump_left ? v_jump : 0));
     v_left--;
   };
 
@@ -255,16 +266,16 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   // Key range of this wave (in 32-key sub-tiles).
   int wave_kv_end = 0;
   if (qw0 < p.Sq) {
-    wave_kv_end = p.Sk;
-    if (causal) wave_kv_end = max(0, min(p.Sk, min(qw0 + 31, p.Sq - 1) + p.causal_off + 1));
+    wave_kv_end = Sk;
+    if (causal) wave_kv_end = max(0, min(Sk, min(qw0 + 31, p.Sq - 1) + causal_off + 1));
   }
   const int jw = (wave_kv_end + SUB - 1) / SUB;  // sub-tiles this wave has visible keys in
   // wave-uniform loop bounds, forced into scalar registers so that every per-step test is one compare
   const int jw_first = __builtin_amdgcn_readfirstlane(jw);                            // last allowed step that opens a tile
   const int jw_in = __builtin_amdgcn_readfirstlane(min(jw, NSUB * n_tiles - 1));      // last allowed step inside a tile
   // a sub-tile starting at kstart needs masking iff kstart > kmask_from
-  int kmask_from_v = p.Sk - SUB;
-  if (causal) kmask_from_v = min(kmask_from_v, qw0 + p.causal_off - SUB + 1);
+  int kmask_from_v = Sk - SUB;
+  if (causal) kmask_from_v = min(kmask_from_v, qw0 + causal_off - SUB + 1);
   const int kmask_from = __builtin_amdgcn_readfirstlane(kmask_from_v);
 
   // Per-lane LDS read offsets.
@@ -353,8 +364,8 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     constexpr unsigned v_imm = decltype(v_imm_c)::value, k_imm_next = decltype(k_imm_next_c)::value;
 
     if (!INNER && kstart > kmask_from) {  // some key of the sub-tile is past Sk or above this wave's first diagonal
-      int limit = p.Sk - 1;
-      if (causal) limit = min(limit, qrow + p.causal_off);
+      int limit = Sk - 1;
+      if (causal) limit = min(limit, qrow + causal_off);
 #pragma unroll
       for (int i = 0; i < 16; i++) {
         const int key = kstart + 8 * (i >> 2) + 4 * hf + (i & 3);
@@ -455,8 +466,9 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
     for (int i = 0; i < NQK; i++) pre[i] = nxt[i];
   };
 
-  // Tiles that are certain to lie before the last tile of the K/V segment need neither the choice
-  // between the two offset sets nor the end-of-stream test.
+  // Tiles that are certain to lie before the last tile of the K/V segment (and not at the end of
+  // the first segment of a pair) need neither the choice between the two offset sets nor the
+  // end-of-stream and change-of-segment tests.
   auto issue_k_inner = [&](int slot) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < IPW; i++) dma16(k_next, k_off[i], slot * TILE_BYTES + (wave * IPW + i) * 1024);
@@ -556,18 +568,27 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   if (1 <= n_tiles) tile_body(1, IC<1 % NS>{}, IC<0>{});
   if (2 <= n_tiles) tile_body(2, IC<2 % NS>{}, IC<0>{});
   if (3 <= n_tiles) tile_body(3, IC<3 % NS>{}, IC<0>{});
+  // Groups of NS tiles: first the groups of inner tiles, then general ones to the end.  With a pair
+  // of segments the sequence runs twice: the groups whose loads (K_{u0+3} .. K_{u0+6}, V_{u0+2} ..
+  // V_{u0+5}) include the last tile of the first segment, after which the stream changes segment,
+  // take the general bodies, and the inner ones resume behind them.
+  const int jump_tile = kseg2 >= 0 ? p.Sk / BN - 1 : 0x40000000;
   int u0 = NS;
-  for (; u0 + NS - 1 <= u_inner; u0 += NS) {
-    tile_body(u0, IC<0>{}, IC<1>{});
-    tile_body(u0 + 1, IC<1 % NS>{}, IC<1>{});
-    tile_body(u0 + 2, IC<2 % NS>{}, IC<1>{});
-    tile_body(u0 + 3, IC<3 % NS>{}, IC<1>{});
-  }
-  for (; u0 <= n_tiles; u0 += NS) {
-    tile_body(u0, IC<0>{}, IC<0>{});
-    if (u0 + 1 <= n_tiles) tile_body(u0 + 1, IC<1 % NS>{}, IC<0>{});
-    if (u0 + 2 <= n_tiles) tile_body(u0 + 2, IC<2 % NS>{}, IC<0>{});
-    if (u0 + 3 <= n_tiles) tile_body(u0 + 3, IC<3 % NS>{}, IC<0>{});
+  for (int half = 0; half < 2; half++) {
+    const int inner_end = half == 0 ? min(u_inner, jump_tile - 4) : u_inner;
+    const int general_end = half == 0 ? min(n_tiles, jump_tile - 2) : n_tiles;
+    for (; u0 + NS - 1 <= inner_end; u0 += NS) {
+      tile_body(u0, IC<0>{}, IC<1>{});
+      tile_body(u0 + 1, IC<1 % NS>{}, IC<1>{});
+      tile_body(u0 + 2, IC<2 % NS>{}, IC<1>{});
+      tile_body(u0 + 3, IC<3 % NS>{}, IC<1>{});
+    }
+    for (; u0 <= general_end; u0 += NS) {
+      tile_body(u0, IC<0>{}, IC<0>{});
+      if (u0 + 1 <= n_tiles) tile_body(u0 + 1, IC<1 % NS>{}, IC<0>{});
+      if (u0 + 2 <= n_tiles) tile_body(u0 + 2, IC<2 % NS>{}, IC<0>{});
+      if (u0 + 3 <= n_tiles) tile_body(u0 + 3, IC<3 % NS>{}, IC<0>{});
+    }
   }
   __builtin_amdgcn_s_waitcnt(0);  // no LDS write of this workgroup may still be in flight at exit
 

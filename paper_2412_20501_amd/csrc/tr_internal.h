@@ -33,13 +33,16 @@ struct AttnParams {
   // Several independent block steps of equal shape in one launch (the steps different "devices"
   // run in the same iteration of a schedule): problem g = blockIdx.z works on the
   // Query segment q_seg[g] (q, out, lse advanced by q_seg[g] * *_seg elements) and the K/V
-  // segment k_seg[g], with the causal rule iff bit g of causal_bits is set.  n_prob = 1 with
-  // q_seg[0] = k_seg[0] = 0 and causal_bits = causal is the plain single step.
+  // segment k_seg[g], with the causal rule iff bit g of causal_bits is set.  k_seg2[g] >= 0 appends
+  // a second K/V segment to the key range of step g (keys Sk .. 2 Sk - 1, lying Sk positions after
+  // the first in the causal rule: with the bit set, query r sees key c iff c <= r + Sk); Sk must
+  // then be a multiple of 128.  n_prob = 1 with q_seg[0] = k_seg[0] = 0, k_seg2[0] = -1 and
+  // causal_bits = causal is the plain single step.
   int n_prob;
   int blocks_per_prob;
   unsigned causal_bits;
   int64_t q_seg_elems, k_seg_elems, v_seg_elems, o_seg_elems, l_seg_elems;
-  short q_seg[kAttnGroupMax], k_seg[kAttnGroupMax];
+  short q_seg[kAttnGroupMax], k_seg[kAttnGroupMax], k_seg2[kAttnGroupMax];
 };
 
 // Arguments of the merge kernel.

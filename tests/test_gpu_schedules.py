@@ -38,6 +38,20 @@ def test_every_schedule_reaches_unchunked_attention(lib, name, n_dev, n_inner, c
     assert max_abs(to_np(out), ref_o) <= OUT_TOL and max_abs(to_np(lse), ref_l) <= LSE_TOL
 
 
+@pytest.mark.parametrize("D,n_dev,seg", [(128, 2, 128), (128, 3, 384), (128, 4, 256), (64, 2, 128), (64, 3, 384), (64, 5, 256)])
+def test_zigzag_attends_the_k_v_pair_of_a_device_in_one_step(lib, D, n_dev, seg):
+    """Segments that are whole K/V tiles: the later Query segment of a pair meets both K/V segments of a
+    device in one block step whose key range changes segment between two tiles (Sec. 3.3.2 partition,
+    Eq. (1)-(3) over the concatenated keys); on iteration 0 the second half carries the diagonal mask."""
+    B, Hq, Hkv, S = 2, 4, 2, 2 * n_dev * seg
+    qb, kb, vb = rand_bits((B, Hq, S, D), 61), rand_bits((B, Hkv, S, D), 62), rand_bits((B, Hkv, S, D), 63)
+    out, lse = _sched(lib, bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb), n_dev, True, lib.TR_SCHED_ZIGZAG, 1)
+    ref_o, ref_l = oracle.attention_full(f64(qb), f64(kb), f64(vb), 1.0 / np.sqrt(D), True)
+    assert max_abs(to_np(out), ref_o) <= OUT_TOL and max_abs(to_np(lse), ref_l) <= LSE_TOL
+    steps = lib.tr_schedule_steps(lib.TR_SCHED_ZIGZAG, n_dev, True)
+    assert max(g for _, _, g in steps) + 1 == n_dev          # one launch per iteration
+
+
 def test_tokenring_schedule_is_tr_ring_attn_bitwise(lib):
     qb, kb, vb = rand_bits((1, 4, 1024, 64), 44), rand_bits((1, 4, 1024, 64), 45), rand_bits((1, 4, 1024, 64), 46)
     q, k, v = bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb)

@@ -53,13 +53,22 @@ def test_launch_grouping_invariants(tr, sched, n, inner, causal):
     assert launches == sorted(launches) and launches[0] == 0 and set(launches) == set(range(launches[-1] + 1))
     seen = set()
     for g in range(launches[-1] + 1):
-        qsegs = [q for q, _, gg in steps if gg == g]
+        in_g = [(q, k) for q, k, gg in steps if gg == g]
+        if sched == 2:
+            # zigzag: a step over the device's K/V pair is listed as two adjacent entries (q, k), (q, 2n-1-k)
+            fused = [a for a, b in zip(in_g, in_g[1:]) if a[0] == b[0]]
+            assert all((q, 2 * n - 1 - k) == in_g[in_g.index((q, k)) + 1] and k < n <= q for q, k in fused)
+            in_g = [e for e in in_g if not any(e == (q, 2 * n - 1 - k) for q, k in fused)]
+            assert len(fused) == n - g                                          # iteration g: the devices whose K/V pair does not lie before the Query pair
+        qsegs = [q for q, _ in in_g]
         assert 1 <= len(qsegs) <= 32 and len(set(qsegs)) == len(qsegs)          # independent steps only
         kinds = {q in seen for q in qsegs}
         assert len(kinds) == 1                                                  # all first blocks, or all later blocks
         seen.update(qsegs)
     if sched == 0 and causal:
         assert launches[-1] + 1 == n                      # Algorithm 1 on contiguous causal chunks: one launch per iteration or fewer
+    if sched == 2:
+        assert launches[-1] + 1 == n                      # zigzag: one launch per iteration
     if sched == 0 and not causal and n <= 32:
         assert launches[-1] + 1 == n                      # every iteration is one launch
 
