@@ -164,8 +164,8 @@ def test_ring_blocks_bf16_transport(lib, causal):
     ref_o, ref_l = oracle.attention_full(f64(qb), f64(kb), f64(vb), 1.0 / np.sqrt(D), causal)
     vmax = float(np.abs(f64(vb)).max())
     d_o, d_l = max_abs(to_np(out), ref_o), max_abs(to_np(lse), ref_l)
-    print(f"bf16 transport, causal={causal}: max|d out| {d_o:.3e} (bound {OUT_TOL + vmax * 2.0 ** -9:.3e}), max|d lse| {d_l:.3e}")
-    assert d_o <= OUT_TOL + vmax * 2.0 ** -9 and d_l <= LSE_TOL
+    print(f"bf16 transport, causal={causal}: max|d out| {d_o:.3e} (bound {OUT_TOL + vmax * 2.0 ** -8:.3e}), max|d lse| {d_l:.3e}")
+    assert d_o <= OUT_TOL + vmax * 2.0 ** -8 and d_l <= LSE_TOL
     # and the same order of Updates with the oracle's blocks rounded to bf16 on the way (first block of a chunk is not)
     C = S // n
     o_ref = np.zeros((B, Hq, S, D)); l_ref = np.full((B, Hq, S), -np.inf)
@@ -194,5 +194,5 @@ def test_ring_config3_bf16_transport_sampled_rows(lib):
     assert not torch.isnan(out).any() and not torch.isnan(lse).any()
     worst_o, worst_l, n = _check_rows(cfg, out, lse, qb, kb, vb, n_random=128)
     vmax = float(np.abs(f64(vb)).max())
-    print(f"cfg3 bf16 transport: {n} rows x {cfg.Hq} heads, max|d out| {worst_o:.3e} (bound {OUT_TOL + vmax * 2.0 ** -9:.3e}), max|d lse| {worst_l:.3e}")
-    assert worst_o <= OUT_TOL + vmax * 2.0 ** -9 and worst_l <= LSE_TOL
+    print(f"cfg3 bf16 transport: {n} rows x {cfg.Hq} heads, max|d out| {worst_o:.3e} (bound {OUT_TOL + vmax * 2.0 ** -8:.3e}), max|d lse| {worst_l:.3e}")
+    assert worst_o <= OUT_TOL + vmax * 2.0 ** -8 and worst_l <= LSE_TOL
