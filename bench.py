@@ -44,6 +44,17 @@ def _traffic(kernel):
         return None
 
 
+def _settle(fn, seconds=0.25):
+    """Untimed: runs the workload itself for a moment, so that what is timed next does not inherit the clock
+    state the previous workload left (a library GEMM leaves the chip slower for tens of milliseconds)."""
+    import torch
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
+
+
 def _median(xs):
     xs = sorted(xs)
     n = len(xs)
@@ -203,6 +214,7 @@ def bench_step_fused(tr, wl, steps, warmup):
     q, k, v = _dev(qb), _dev(kb), _dev(vb)
     acc_o = torch.zeros((cfg.B, cfg.Hq, cfg.S, cfg.D), dtype=torch.float32, device="cuda")
     acc_l = torch.full((cfg.B, cfg.Hq, cfg.S), float("-inf"), dtype=torch.float32, device="cuda")
+    _settle(lambda: tr.tr_block_attn_merge(q, k, v, tr.TR_MASK_NONE, cfg.scale, acc_o, acc_l))
     for _ in range(warmup):
         tr.tr_block_attn_merge(q, k, v, tr.TR_MASK_NONE, cfg.scale, acc_o, acc_l)
     torch.cuda.synchronize()
@@ -233,6 +245,7 @@ def bench_block(tr, wl, name, steps, warmup, what):
     blk_o = torch.empty((cfg.B, cfg.Hq, cfg.S, cfg.D), dtype=torch.bfloat16, device="cuda")
     blk_l = torch.empty((cfg.B, cfg.Hq, cfg.S), dtype=torch.float32, device="cuda")
     mask = tr.TR_MASK_CAUSAL_DIAG if cfg.causal else tr.TR_MASK_NONE
+    _settle(lambda: tr.tr_block_attn(q, k, v, mask, cfg.scale, blk_o, blk_l))
     for _ in range(warmup):
         tr.tr_block_attn(q, k, v, mask, cfg.scale, blk_o, blk_l)
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
