@@ -238,3 +238,12 @@ def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
     with pytest.raises(ImportError):
         b._load()
     importlib.reload(b)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU's share of the path; any other --gpus value ends with a message, before torch is touched."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert res.returncode == 2 and "single-GPU" in res.stderr and res.stdout.strip() == ""
