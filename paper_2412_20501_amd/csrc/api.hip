@@ -180,6 +180,10 @@ tr_status attn_common(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v
     }
   }
   if ((int64_t)p.blocks_per_prob * p.n_prob >= ((int64_t)1 << 31)) return fail(TR_ERR_SHAPE, "too many workgroups for one launch");
+  // Without a causal step in the launch all query tiles cost the same, and an XCD may finish the
+  // query tiles of one head before it starts the next: half as many heads' K/V are then live in
+  // its L2 at a time.  (Under a causal mask that order would bunch the heavy tiles.)
+  if (p.xcd_map && p.causal_bits == 0 && (int64_t)p.B * p.Hq / 8 <= 65535) p.xcd_map = 2;
   if (p.B == 0 || p.Hq == 0 || p.Sq == 0) return TR_OK;
   const int epilogue = fuse_update ? 2 : (out->dtype == TR_F32 ? 1 : 0);
   const hipError_t e = tr::launch_block_attn(p, (int)q->D, epilogue, (hipStream_t)stream);

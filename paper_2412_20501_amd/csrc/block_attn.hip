@@ -102,9 +102,13 @@ __device__ __forceinline__ int v_lds_off(int row, int c) {
 // all query heads and query tiles that read them, so a head's K/V stays in one L2.
 __device__ __forceinline__ void decode_block(const AttnParams& p, int& qt, int& b, int& hq, int& hk, int& prob) {
   const int gq = p.gq, sh = p.gq_log2;   // query heads per K/V head; its log2, or -1 if not a power of two
-  int bh = (int)blockIdx.x;
+  int bh = (int)blockIdx.x, qi = (int)blockIdx.y;
   if (p.xcd_map) {
-    const int x = bh & 7, hi = bh >> 3;
+    int x = bh & 7, hi = bh >> 3;
+    if (p.xcd_map == 2) {   // x = XCD + 8 * query tile, y = head within the XCD
+      qi = hi;
+      hi = (int)blockIdx.y;
+    }
     const int kvi = sh >= 0 ? hi >> sh : hi / gq;
     const int mem = sh >= 0 ? hi & (gq - 1) : hi % gq;
     bh = (kvi * 8 + x) * gq + mem;
@@ -112,7 +116,7 @@ __device__ __forceinline__ void decode_block(const AttnParams& p, int& qt, int& 
   b = p.B == 1 ? 0 : bh / p.Hq;
   hq = bh - b * p.Hq;
   hk = sh >= 0 ? hq >> sh : hq / gq;
-  qt = p.n_qtiles - 1 - (int)blockIdx.y;  // late query tiles (most keys under a causal mask) first
+  qt = p.n_qtiles - 1 - qi;  // late query tiles (most keys under a causal mask) first
   prob = (int)blockIdx.z;
 }
 
@@ -725,6 +729,7 @@ hipError_t launch_block_attn(const AttnParams& p, int D, int epilogue, hipStream
   if (nbh * p.n_qtiles * p.n_prob == 0) return hipSuccess;
   if (p.n_qtiles > 65535 || p.n_prob > 65535) return hipErrorInvalidValue;   // grid y / z limits
   dim3 grid((unsigned)nbh, (unsigned)p.n_qtiles, (unsigned)p.n_prob);
+  if (p.xcd_map == 2) grid = dim3(8u * (unsigned)p.n_qtiles, (unsigned)(nbh / 8), (unsigned)p.n_prob);
   if (D == 128) {
     if (epilogue == kEpiBf16) return launch_one<128, kEpiBf16>(p, grid, stream);
     if (epilogue == kEpiF32) return launch_one<128, kEpiF32>(p, grid, stream);

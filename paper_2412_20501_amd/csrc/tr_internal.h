@@ -27,7 +27,7 @@ struct AttnParams {
   int causal_off; // q_pos0 - k_pos0, clamped so that r + causal_off cannot overflow
   float scale;    // softmax scale (natural units)
   int n_qtiles;   // ceil(Sq / rows per workgroup)
-  int xcd_map;    // 1: place all query tiles of a K/V head on one XCD
+  int xcd_map;    // 1: place all query tiles of a K/V head on one XCD (grid x = batch*head, y = query tile); 2: the same with grid x = XCD + 8 * query tile, y = head within the XCD
   int gq;         // query heads per K/V head (Hq / Hkv)
   int gq_log2;    // log2(gq) if gq is a power of two, else -1
   // Several independent block steps of equal shape in one launch (the steps different "devices"
