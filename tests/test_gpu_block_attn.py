@@ -37,6 +37,8 @@ SHAPES = [
     (1, 3, 3, 33, 500, 64),       # Sq < one wave, several K/V tiles + tail
     (1, 2, 2, 513, 65, 128),      # three query tiles (last nearly empty), key tail of 1
     (1, 8, 8, 512, 1024, 128),    # exercises the XCD-aware block mapping
+    (1, 24, 8, 300, 300, 128),    # XCD-aware mapping with three query heads per K/V head (not a power of two)
+    (2, 16, 8, 260, 260, 64),     # XCD-aware mapping with batch 2 (16 K/V heads over 8 XCDs), head dim 64
 ]
 
 
@@ -49,6 +51,25 @@ def test_block_attn_no_mask(lib, shape, out_dtype):
     out, lse = _run_block(lib, qb, kb, vb, scale, lib.TR_MASK_NONE, out_dtype)
     ref_o, ref_l = oracle.attention_block(f64(qb), f64(kb), f64(vb), scale)
     assert max_abs(out, ref_o) <= OUT_TOL and max_abs(lse, ref_l) <= LSE_TOL
+
+
+def test_block_attn_more_heads_than_the_head_major_grid_holds(lib):
+    """B * Hq / 8 beyond 65535 (the y extent of a grid): the launch keeps batch*head in x.  Sampled heads against the oracle."""
+    B, H, Sq, Sk, D = 1, 8 * 65537, 2, 3, 64
+    g = torch.Generator(device="cuda").manual_seed(77)
+    q = torch.randn((B, H, Sq, D), device="cuda", generator=g).bfloat16()
+    k = torch.randn((B, H, Sk, D), device="cuda", generator=g).bfloat16()
+    v = torch.randn((B, H, Sk, D), device="cuda", generator=g).bfloat16()
+    out = torch.full((B, H, Sq, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((B, H, Sq), float("nan"), dtype=torch.float32, device="cuda")
+    lib.tr_block_attn(q, k, v, lib.TR_MASK_NONE, 0.125, out, lse)
+    torch.cuda.synchronize()
+    assert not torch.isnan(out).any() and not torch.isnan(lse).any()
+    heads = sorted({0, 1, 7, 8, 9, 65535, 65536, 65537, 8 * 65535, 8 * 65536 - 1, 8 * 65536, H - 9, H - 8, H - 1} | set(range(100000, H, 77773)))
+    hs = torch.tensor(heads, device="cuda")
+    sel = lambda t: t.index_select(1, hs).float().cpu().numpy().astype(np.float64)
+    ref_o, ref_l = oracle.attention_block(sel(q), sel(k), sel(v), 0.125)
+    assert max_abs(sel(out), ref_o) <= OUT_TOL and max_abs(lse.index_select(1, hs).cpu().numpy().astype(np.float64), ref_l) <= LSE_TOL
 
 
 @pytest.mark.parametrize("shape", [s for s in SHAPES if s[3] == s[4]] + [(1, 2, 2, 1000, 1000, 128)])
