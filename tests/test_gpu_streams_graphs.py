@@ -62,3 +62,26 @@ def test_ring_schedule_captured_in_a_graph_replays_exactly(lib, fused):
     graph.replay()
     torch.cuda.synchronize()
     assert torch.equal(out, eager_o) and torch.equal(lse, eager_l)
+
+
+def test_zigzag_schedule_with_paired_segments_replays_from_a_graph(lib):
+    """The zigzag order on 128-key segments (block steps over a device's K/V pair, steps of a launch sorted by length)
+    captured once and replayed with eager work in between: every replay equals the eager result bitwise."""
+    qb, kb, vb = rand_bits((1, 4, 1024, 128), 91), rand_bits((1, 2, 1024, 128), 92), rand_bits((1, 2, 1024, 128), 93)
+    q, k, v = bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb)
+    shape_o, shape_l = (1, 4, 1024, 128), (1, 4, 1024)
+    eager_o = torch.empty(shape_o, dtype=torch.float32, device="cuda"); eager_l = torch.empty(shape_l, device="cuda")
+    lib.tr_ring_attn_sched(q, k, v, 4, True, lib.TR_SCHED_ZIGZAG, eager_o, eager_l)
+    torch.cuda.synchronize()
+    ref_o, ref_l = oracle.attention_full(f64(qb), f64(kb), f64(vb), 1.0 / np.sqrt(128), True)
+    assert max_abs(to_np(eager_o), ref_o) <= 1e-2 and max_abs(to_np(eager_l), ref_l) <= 1e-3
+    out = torch.zeros(shape_o, dtype=torch.float32, device="cuda"); lse = torch.zeros(shape_l, device="cuda")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lib.tr_ring_attn_sched(q, k, v, 4, True, lib.TR_SCHED_ZIGZAG, out, lse)
+    for replay in range(3):
+        out.fill_(float("nan")); lse.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager_o) and torch.equal(lse, eager_l), f"replay {replay}"
