@@ -52,6 +52,42 @@ def test_zigzag_attends_the_k_v_pair_of_a_device_in_one_step(lib, D, n_dev, seg)
     assert max(g for _, _, g in steps) + 1 == n_dev          # one launch per iteration
 
 
+def _random_schedule_cases(n_cases, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n_cases):
+        sched = int(rng.integers(0, 4))
+        n_dev = int(rng.choice([1, 2, 3, 4, 6, 8]))
+        n_inner = 1
+        if sched == 3:
+            n_inner = int(rng.choice([d for d in (1, 2, 3, 4) if n_dev % d == 0]))
+        causal = True if sched == 2 else bool(rng.integers(0, 2))
+        seg = int(rng.choice([40, 64, 128, 128, 256, 384]))          # 128-multiples take the paired zigzag steps
+        n_seg = 2 * n_dev if sched == 2 else n_dev
+        while n_seg * seg > 3072:
+            seg //= 2
+        D = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2, 8]))
+        G = int(rng.choice([1, 2, 3]))
+        B = int(rng.choice([1, 2])) if Hkv < 8 else 1
+        cases.append((i, sched, n_dev, n_inner, causal, seg, D, Hkv, G, B))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_schedule_cases(28, 20261),
+                         ids=lambda c: f"{c[0]}-sched{c[1]}-n{c[2]}x{c[3]}-{'causal' if c[4] else 'full'}-seg{c[5]}-D{c[6]}-Hkv{c[7]}x{c[8]}-B{c[9]}")
+def test_seeded_random_schedules_reach_unchunked_attention(lib, case):
+    """Seeded sweep over schedule, device count, segment length (ragged and whole tiles), head dim, GQA group
+    (including 3) and batch: every combination must reach unchunked fp64 attention."""
+    i, sched, n_dev, n_inner, causal, seg, D, Hkv, G, B = case
+    n_seg = 2 * n_dev if sched == 2 else n_dev
+    S, Hq = n_seg * seg, Hkv * G
+    qb, kb, vb = rand_bits((B, Hq, S, D), 700 + 3 * i), rand_bits((B, Hkv, S, D), 701 + 3 * i), rand_bits((B, Hkv, S, D), 702 + 3 * i)
+    out, lse = _sched(lib, bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb), n_dev, causal, sched, n_inner)
+    ref_o, ref_l = oracle.attention_full(f64(qb), f64(kb), f64(vb), 1.0 / np.sqrt(D), causal)
+    assert max_abs(to_np(out), ref_o) <= OUT_TOL and max_abs(to_np(lse), ref_l) <= LSE_TOL
+
+
 def test_tokenring_schedule_is_tr_ring_attn_bitwise(lib):
     qb, kb, vb = rand_bits((1, 4, 1024, 64), 44), rand_bits((1, 4, 1024, 64), 45), rand_bits((1, 4, 1024, 64), 46)
     q, k, v = bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb)
