@@ -165,7 +165,7 @@ tr_status tr_ring_attn(const tr_tensor* q, const tr_tensor* k, const tr_tensor* 
  * Algorithm 1 in its literal two-kernel form with a chosen format for the block result that
  * travels between the Attention and the Update (Sec. 3.1 notes the volume of block_out and
  * block_lse): block_dtype = TR_F32 is tr_ring_attn with a workspace; TR_BF16 halves block_out
- * (what a multi-device run would put on the wire) at the cost of one bf16 rounding (2^-9
+ * (what a multi-device run would put on the wire) at the cost of one bf16 rounding (at most 2^-8
  * relative) of every block before it is merged.  block_lse stays fp32.  The workspace is
  * required, 256-byte aligned, at least tr_ring_attn_blocks_workspace_bytes(q, n_chunks,
  * block_dtype) bytes.  Everything else as in tr_ring_attn.

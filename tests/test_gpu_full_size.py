@@ -16,7 +16,7 @@ def test_config2_block_step_4096x4096(lib, name):
     """bf16 block_out + fp32 block_lse.  Four heads are checked in full, the rest on sampled rows.
 
     block_out is rounded to bf16 on output, so its error against the oracle includes half a
-    bf16 ulp of the value itself (up to 2^-9 relative); it is also reported against the
+    bf16 ulp of the value itself (up to 2^-8 relative); it is also reported against the
     oracle rounded to bf16.
     """
     cfg = wl.CONFIGS[name]

@@ -150,7 +150,7 @@ def test_ring_blocks_fp32_is_the_two_kernel_form_bitwise(lib):
 @pytest.mark.parametrize("causal", [False, True])
 def test_ring_blocks_bf16_transport(lib, causal):
     """block_out stored as bf16 between Attention and Update: every merged block carries one bf16 rounding,
-    i.e. at most 2^-9 of the largest block value on top of the kernel's own 1e-2; lse is untouched by it."""
+    i.e. at most 2^-8 of the largest block value on top of the kernel's own 1e-2; lse is untouched by it."""
     B, Hq, Hkv, S, D, n = 1, 4, 2, 1024, 128, 4
     qb, kb, vb = rand_bits((B, Hq, S, D), 53), rand_bits((B, Hkv, S, D), 54), rand_bits((B, Hkv, S, D), 55)
     q, k, v = bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb)
