@@ -215,7 +215,7 @@ typedef enum {
  *                           (three on i == 0, two of them diagonal), so every (i, j) carries the same work.  When the
  *                           later Query segment meets both K/V segments of the device and the segment length is a
  *                           multiple of 128, the two are attended in ONE block step over the device's whole K/V (one
- *                           softmax over both, one Update), which Eq. (1)-(3) leave unchanged; an iteration is then
+ *                           softmax over both, one Update), which leaves the result of Sec. 3.1's Update unchanged; an iteration is then
  *                           a single launch of at most two steps per device.  Otherwise the devices' pairs are issued
  *                           slot by slot (all first pairs, then all second, ...)
  *   TR_SCHED_HYBRID         n_devices = nodes x n_inner; for t < nodes, for i < n_inner, for node, for p:

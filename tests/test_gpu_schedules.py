@@ -42,7 +42,7 @@ def test_every_schedule_reaches_unchunked_attention(lib, name, n_dev, n_inner, c
 def test_zigzag_attends_the_k_v_pair_of_a_device_in_one_step(lib, D, n_dev, seg):
     """Segments that are whole K/V tiles: the later Query segment of a pair meets both K/V segments of a
     device in one block step whose key range changes segment between two tiles (Sec. 3.3.2 partition,
-    Eq. (1)-(3) over the concatenated keys); on iteration 0 the second half carries the diagonal mask."""
+    attention and its log-sum-exp, Sec. 3.1, over the concatenated keys); on iteration 0 the second half carries the diagonal mask."""
     B, Hq, Hkv, S = 2, 4, 2, 2 * n_dev * seg
     qb, kb, vb = rand_bits((B, Hq, S, D), 61), rand_bits((B, Hkv, S, D), 62), rand_bits((B, Hkv, S, D), 63)
     out, lse = _sched(lib, bits_to_dev(qb), bits_to_dev(kb), bits_to_dev(vb), n_dev, True, lib.TR_SCHED_ZIGZAG, 1)
