@@ -5,9 +5,10 @@ One JSON line on stdout.  A *step* is one iteration of Algorithm 1 on one device
 4096 x 4096, 32-head, D=128 block shape: tr_block_attn (bf16 block_out + fp32 block_lse)
 followed by tr_merge of that block into the fp32 accumulators.  `value` is the step's
 attention TFLOP (4*Sq*Sk*D per head) divided by the whole step time, inputs resident in
-HBM.  `roofline` is the block-attention kernel against the bf16 MFMA peak, from HIP-event
-durations carried by every launch of the timed region; `merge_roofline` is the same for the
-merge kernel against HBM.  `parity` holds the max-abs errors of the same step against the
+HBM.  `roofline` is the block-attention kernel against the bf16 MFMA peak, from HIP events
+carried by every launch of a second pass over the same K steps right after the timed one (a
+launch that carries events costs the host more, which is not the step's cost);
+`merge_roofline` is the same for the merge kernel against HBM.  `parity` holds the max-abs errors of the same step against the
 fp64 oracle on four heads.  `extras` adds the library GEMM's rate on this machine, the fused
 step, the block step on other score distributions, the merge-only bandwidth workload
 (pairwise and n-ary), the ring-schedule workloads and oracle timings of the other
