@@ -656,45 +656,65 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
       }
     }
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the wave's own LDS writes are visible to all its lanes
+    // All LDS reads of the wave's rows go out first (block piece, weight and case of its row), then
+    // the pieces are blended and stored; the row address advances by a fixed step.
+    f32x4 ov[NIT];
+    UpdatePlan pl[NIT];
 #pragma unroll
     for (int it = 0; it < NIT; it++) {
       const int r = it * RPI_OUT + rr;
-      const int grow = qw0 + r;
-      const f32x4 o = *reinterpret_cast<const f32x4*>(my + r * ROWB + ((cc ^ (r & 15)) << 4));
-      UpdatePlan pl;
-      pl.w = my_w[r];
-      pl.mode = my_mode[r];
-      pl.new_lse = 0.f;
-      if (grow < p.Sq)
-        __builtin_nontemporal_store(apply_update(pl, x[it], o), reinterpret_cast<f32x4*>(acc_out + o_bh + (int64_t)grow * p.o_ss));
+      ov[it] = *reinterpret_cast<const f32x4*>(my + r * ROWB + ((cc ^ (r & 15)) << 4));
+      pl[it].w = my_w[r];
+      pl[it].mode = my_mode[r];
+      pl[it].new_lse = 0.f;
+    }
+    float* dst = acc_out + o_bh + (int64_t)(qw0 + rr) * p.o_ss;
+    const int64_t dst_step = (int64_t)RPI_OUT * p.o_ss;
+#pragma unroll
+    for (int it = 0; it < NIT; it++) {
+      if (qw0 + it * RPI_OUT + rr < p.Sq) __builtin_nontemporal_store(apply_update(pl[it], x[it], ov[it]), reinterpret_cast<f32x4*>(dst));
+      dst += dst_step;
     }
   } else if (EPI == kEpiF32) {
+    f32x4 ov[NIT];
 #pragma unroll
     for (int it = 0; it < NIT; it++) {
       const int r = it * RPI_OUT + rr;
-      const int grow = qw0 + r;
-      const f32x4 o = *reinterpret_cast<const f32x4*>(my + r * ROWB + ((cc ^ (r & 15)) << 4));
-      if (grow < p.Sq) *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + o_bh + (int64_t)grow * p.o_ss) = o;
+      ov[it] = *reinterpret_cast<const f32x4*>(my + r * ROWB + ((cc ^ (r & 15)) << 4));
+    }
+    float* dst = reinterpret_cast<float*>(p.out) + o_bh + (int64_t)(qw0 + rr) * p.o_ss;
+    const int64_t dst_step = (int64_t)RPI_OUT * p.o_ss;
+#pragma unroll
+    for (int it = 0; it < NIT; it++) {
+      if (qw0 + it * RPI_OUT + rr < p.Sq) *reinterpret_cast<f32x4*>(dst) = ov[it];
+      dst += dst_step;
     }
   } else {
     // bf16 rows are half as long: a lane converts two neighbouring chunks and stores 16 bytes
     constexpr int LPR = D / 8;          // lanes per bf16 row
     constexpr int RPI_B = 64 / LPR;     // rows one wave-wide store covers
+    constexpr int NIT_B = 32 / RPI_B;
     const int rb = lane / LPR, cb = lane % LPR;
     const int64_t ob_bh = qseg * p.o_seg_elems + (int64_t)b * p.o_sb + (int64_t)hq * p.o_sh + 8 * cb;
+    f32x4 o0[NIT_B], o1[NIT_B];
 #pragma unroll
-    for (int it = 0; it < 32 / RPI_B; it++) {
+    for (int it = 0; it < NIT_B; it++) {
       const int r = it * RPI_B + rb;
-      const int grow = qw0 + r;
-      const f32x4 o0 = *reinterpret_cast<const f32x4*>(my + r * ROWB + (((2 * cb) ^ (r & 15)) << 4));
-      const f32x4 o1 = *reinterpret_cast<const f32x4*>(my + r * ROWB + (((2 * cb + 1) ^ (r & 15)) << 4));
+      o0[it] = *reinterpret_cast<const f32x4*>(my + r * ROWB + (((2 * cb) ^ (r & 15)) << 4));
+      o1[it] = *reinterpret_cast<const f32x4*>(my + r * ROWB + (((2 * cb + 1) ^ (r & 15)) << 4));
+    }
+    __bf16* dst = reinterpret_cast<__bf16*>(p.out) + ob_bh + (int64_t)(qw0 + rb) * p.o_ss;
+    const int64_t dst_step = (int64_t)RPI_B * p.o_ss;
+#pragma unroll
+    for (int it = 0; it < NIT_B; it++) {
       bf16x8 ob;
 #pragma unroll
       for (int k = 0; k < 4; k++) {
-        ob[k] = (__bf16)o0[k];
-        ob[4 + k] = (__bf16)o1[k];
+        ob[k] = (__bf16)o0[it][k];
+        ob[4 + k] = (__bf16)o1[it][k];
       }
-      if (grow < p.Sq) *reinterpret_cast<bf16x8*>(reinterpret_cast<__bf16*>(p.out) + ob_bh + (int64_t)grow * p.o_ss) = ob;
+      if (qw0 + it * RPI_B + rb < p.Sq) *reinterpret_cast<bf16x8*>(dst) = ob;
+      dst += dst_step;
     }
   }
 }

@@ -124,15 +124,23 @@ __device__ __forceinline__ UpdatePlan plan_update(float lse_acc, float lse_blk) 
   }
   return r;
 }
+// Branch-free: the blend is evaluated for every lane and bit masks made from the plan's case pick
+// the result among blend, block, accumulator and zero, so whatever NaN or Inf an uninitialised
+// side holds never reaches it and no lane waits for another's case.
 __device__ __forceinline__ tr_f32x4 apply_update(const UpdatePlan& pl, tr_f32x4 acc, tr_f32x4 blk) {
-  if (pl.mode == 0) {
-    tr_f32x4 o;
+  const unsigned m_blend = pl.mode == 0 ? 0xffffffffu : 0u;
+  const unsigned m_blk = pl.mode == 2 ? 0xffffffffu : 0u;
+  const unsigned m_acc = pl.mode == 3 ? 0xffffffffu : 0u;
+  tr_f32x4 o;
 #pragma unroll
-    for (int i = 0; i < 4; i++) o[i] = acc[i] + pl.w * (blk[i] - acc[i]);
-    return o;
+  for (int i = 0; i < 4; i++) {
+    const float a = acc[i], y = blk[i];   // scalars: a bit cast must not be applied to a vector element directly
+    const float blend = __builtin_fmaf(pl.w, y - a, a);
+    const unsigned bits = (m_blend & __builtin_bit_cast(unsigned, blend)) | (m_blk & __builtin_bit_cast(unsigned, y)) |
+                          (m_acc & __builtin_bit_cast(unsigned, a));
+    o[i] = __builtin_bit_cast(float, bits);
   }
-  if (pl.mode == 1) return tr_f32x4{0.f, 0.f, 0.f, 0.f};
-  return pl.mode == 2 ? blk : acc;
+  return o;
 }
 #endif
 
