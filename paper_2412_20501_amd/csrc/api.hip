@@ -154,7 +154,7 @@ tr_status attn_common(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v
     if (p.gq == (1 << sh)) p.gq_log2 = sh;
   if (p.n_qtiles > 65535) return fail(TR_ERR_SHAPE, "Sq too long for one launch (at most 65535 query tiles of %d rows)", bm);
   p.n_prob = 1;
-  for (int i = 0; i < tr::kAttnGroupMax; i++) p.k_seg2[i] = -1;
+  for (int i = 0; i < tr::kAttnGroupMax; i++) p.step[i].k_seg2 = -1;
   p.blocks_per_prob = p.n_qtiles * p.B * p.Hq;
   p.causal_bits = p.causal ? 1u : 0u;
   if (group) {
@@ -173,9 +173,9 @@ tr_status attn_common(const tr_tensor* q, const tr_tensor* k, const tr_tensor* v
     for (int i = 0; i < group->n; i++) {
       const RingStep& s = *order[i];
       if (s.ks2 >= 0 && (group->seg_len % 128 || s.ks2 <= s.ks)) return fail(TR_ERR_SHAPE, "internal: segment pair on segments of %lld keys", (long long)group->seg_len);
-      p.q_seg[i] = (short)s.qs;
-      p.k_seg[i] = (short)s.ks;
-      p.k_seg2[i] = (short)s.ks2;
+      p.step[i].q_seg = s.qs;
+      p.step[i].k_seg = s.ks;
+      p.step[i].k_seg2 = s.ks2;
       if (group->causal && (s.ks2 >= 0 ? s.ks2 : s.ks) == s.qs) p.causal_bits |= 1u << i;
     }
   }

@@ -165,13 +165,14 @@ __global__ void __launch_bounds__(kThreads) block_attn_kernel(const AttnParams p
   // which block step of the launch, batch, head and query tile this workgroup computes (wave-uniform)
   int qt, b, hq, hk, prob;
   decode_block(p, qt, b, hq, hk, prob);
-  const int64_t qseg = p.q_seg[prob], kseg = p.k_seg[prob];
+  const AttnParams::Step sg = p.step[prob];
+  const int64_t qseg = sg.q_seg, kseg = sg.k_seg;
   const bool causal = (p.causal_bits >> prob) & 1u;
   // A block step may attend a pair of K/V segments as one key range (the two segments a device of
   // the zigzag partition holds): keys 0 .. p.Sk-1 are segment kseg, keys p.Sk .. 2 p.Sk-1 segment
   // kseg2, which lies p.Sk positions later in the causal rule.  p.Sk is then a multiple of the
   // tile, so the tile stream changes segment between two tiles.
-  const int kseg2 = p.k_seg2[prob];
+  const int kseg2 = sg.k_seg2;
   const int Sk = kseg2 >= 0 ? 2 * p.Sk : p.Sk;
   const int causal_off = kseg2 >= 0 ? p.Sk : p.causal_off;
   const int q0 = qt * kBM, qw0 = q0 + wave * 32;

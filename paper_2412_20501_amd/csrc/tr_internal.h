@@ -32,17 +32,19 @@ struct AttnParams {
   int gq_log2;    // log2(gq) if gq is a power of two, else -1
   // Several independent block steps of equal shape in one launch (the steps different "devices"
   // run in the same iteration of a schedule): problem g = blockIdx.z works on the
-  // Query segment q_seg[g] (q, out, lse advanced by q_seg[g] * *_seg elements) and the K/V
-  // segment k_seg[g], with the causal rule iff bit g of causal_bits is set.  k_seg2[g] >= 0 appends
+  // Query segment step[g].q_seg (q, out, lse advanced by q_seg * *_seg elements) and the K/V
+  // segment step[g].k_seg, with the causal rule iff bit g of causal_bits is set.  k_seg2 >= 0 appends
   // a second K/V segment to the key range of step g (keys Sk .. 2 Sk - 1, lying Sk positions after
   // the first in the causal rule: with the bit set, query r sees key c iff c <= r + Sk); Sk must
-  // then be a multiple of 128.  n_prob = 1 with q_seg[0] = k_seg[0] = 0, k_seg2[0] = -1 and
-  // causal_bits = causal is the plain single step.
+  // then be a multiple of 128.  n_prob = 1 with step[0] = {0, 0, -1} and causal_bits = causal is
+  // the plain single step.  (One 16-byte record per step: the workgroup fetches it with a single
+  // scalar load at a wave-uniform offset; arrays of 16-bit entries would be read through the
+  // vector memory path, a round trip to the memory-side caches in front of the first K/V load.)
   int n_prob;
   int blocks_per_prob;
   unsigned causal_bits;
   int64_t q_seg_elems, k_seg_elems, v_seg_elems, o_seg_elems, l_seg_elems;
-  short q_seg[kAttnGroupMax], k_seg[kAttnGroupMax], k_seg2[kAttnGroupMax];
+  struct Step { int q_seg, k_seg, k_seg2, pad; } step[kAttnGroupMax];
 };
 
 // Arguments of the merge kernel.
